@@ -1,0 +1,318 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged decode step on one MI355X.
+
+A step is one pass of the whole hot path over one admitted batch: KV append of
+every job's new token, then one-query-per-job attention over every job's paged
+cache (partition pass + combine).  Inputs are synthetic and seeded
+(fs_workload), resident in HBM before the timed region.  To keep the 256 MB
+last-level cache from serving the reads, the steps rotate over several replicas
+of the pool.
+
+Prints ONE JSON line; see --help for the knobs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "decode-attention achieved HBM GB/s (% of MI355X peak); job-tokens/s per step"
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+
+
+def algorithmic_bytes(cfg, lens) -> int:
+    """Bytes one attention launch has to move: every cached K and V element once,
+    q once, out once, each job's table entries and length once."""
+    H, D, e = cfg.num_heads, cfg.head_dim, cfg.elem_bytes
+    total = int(lens.astype(np.int64).sum())
+    nb = int(((lens.astype(np.int64) + cfg.block_size - 1) // cfg.block_size).sum())
+    J = len(lens)
+    return 2 * H * D * e * total + J * H * D * e + J * H * D * 4 + 4 * nb + 4 * J
+
+
+class Replicas:
+    """R copies of one workload's pool in HBM, each behind its own fs_pool."""
+
+    def __init__(self, fs, torch, wl, cfg, rep, min_footprint_bytes, pool_kw, log):
+        self.fs, self.torch, self.cfg = fs, torch, cfg
+        step = wl.make_step(cfg, rep)
+        self.step = step
+        bt = step.tables
+        H, D = cfg.num_heads, cfg.head_dim
+        block_elems = 2 * H * cfg.block_size * D
+        pool_bytes = bt.num_blocks * block_elems * cfg.elem_bytes
+        self.alg_bytes = algorithmic_bytes(cfg, step.lens)
+        R = max(2, int(np.ceil(min_footprint_bytes / max(self.alg_bytes, 1))))
+        R = min(R, max(2, int(24e9 // pool_bytes)))
+        self.R = R
+        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        self.mem = torch.empty((R, bt.num_blocks, block_elems), dtype=tdt, device="cuda")
+        self.pools = [fs.Pool(cfg.dtype, H, D, bt.num_blocks, device_mem=self.mem[r], **pool_kw)
+                      for r in range(R)]
+        self.table = torch.from_numpy(bt.table).cuda()
+        self.lens = torch.from_numpy(step.lens).cuda()
+        lens_before = (step.lens - 1).astype(np.int32)
+        self.lens_before = torch.from_numpy(lens_before).cuda()
+        self.max_len = int(step.lens.max())
+        # host caches -> packed prefix tokens -> bulk write into replica 0 -> copy to the rest
+        t0 = time.time()
+        self.caches = [step.cache(j) for j in range(cfg.num_jobs)]
+        log(f"generated {cfg.name}: J={cfg.num_jobs} sum(L)={step.total_tokens} "
+            f"pool={pool_bytes / 1e9:.2f} GB x{R} in {time.time() - t0:.1f}s")
+        offs = np.zeros(cfg.num_jobs + 1, dtype=np.int32)
+        offs[1:] = np.cumsum(lens_before)
+        self.q = self._dev(step.q)
+        self.k_new = self._dev(np.stack([K[-1] for K, _ in self.caches]))
+        self.v_new = self._dev(np.stack([V[-1] for _, V in self.caches]))
+        # bulk write in slices of jobs so that the packed staging copy stays small
+        j = 0
+        while j < cfg.num_jobs:
+            j1, tok = j, 0
+            while j1 < cfg.num_jobs and (tok == 0 or tok + lens_before[j1] <= (1 << 21)):
+                tok += int(lens_before[j1])
+                j1 += 1
+            if tok > 0:
+                K = np.concatenate([self.caches[i][0][:lens_before[i]] for i in range(j, j1)])
+                V = np.concatenate([self.caches[i][1][:lens_before[i]] for i in range(j, j1)])
+                o = (offs[j:j1 + 1] - offs[j]).astype(np.int32)
+                fs.fs_kv_prefill(self.pools[0], self.table[j:j1].contiguous(),
+                                 torch.zeros(j1 - j, dtype=torch.int32, device="cuda"),
+                                 torch.from_numpy(o).cuda(), tok, self._dev(K), self._dev(V))
+                torch.cuda.synchronize()
+            j = j1
+        self.pools[0].check()
+        for r in range(1, R):
+            self.mem[r].copy_(self.mem[0])
+        self.out = torch.empty((cfg.num_jobs, H, D), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+
+    def _dev(self, a):
+        t = self.torch
+        if self.cfg.dtype == "bf16":
+            return t.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(t.bfloat16)
+        return t.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def run_step(self, i):
+        pool = self.pools[i % self.R]
+        self.fs.fs_kv_append(pool, self.table, self.lens_before, self.k_new, self.v_new)
+        self.fs.fs_decode_attention(self.q, pool, self.table, self.lens, self.out, max_len_hint=self.max_len)
+
+    def close(self):
+        for p in self.pools:
+            p.close()
+
+
+def time_steps(torch, reps, steps, warmup):
+    for i in range(warmup):
+        reps.run_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        reps.run_step(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_times(torch, reps, steps):
+    """Average duration of each kernel, from HIP events the library records on the
+    launch stream around every launch."""
+    for p in reps.pools:
+        p.profile_enable(True)
+    for i in range(steps):
+        reps.run_step(i)
+    torch.cuda.synchronize()
+    tot = {}
+    for p in reps.pools:
+        for kind, rec in p.profile_collect().items():
+            a = tot.setdefault(kind, {"ms": 0.0, "launches": 0})
+            a["ms"] += rec["ms"]
+            a["launches"] += rec["launches"]
+        p.profile_enable(False)
+    return {k: (v["ms"] / v["launches"] if v["launches"] else None) for k, v in tot.items()}
+
+
+def graph_ms(torch, reps, steps):
+    """The same steps replayed from one captured HIP graph (R steps per replay)."""
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for i in range(reps.R):
+            reps.run_step(i)
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        for i in range(reps.R):
+            reps.run_step(i)
+    n = max(1, steps // reps.R)
+    g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (n * reps.R)
+
+
+def cpu_baseline(reps, budget_s=12.0):
+    """The fp64 oracle, as it stands, on this host: whole step (append + attention)."""
+    import oracle
+    cfg, step = reps.cfg, reps.step
+    k_new = np.stack([K[-1] for K, _ in reps.caches])
+    v_new = np.stack([V[-1] for _, V in reps.caches])
+
+    def fresh():
+        lc = oracle.LogicalCaches(cfg.dtype, cfg.num_heads, cfg.head_dim)
+        for K, V in reps.caches:
+            lc.add_job(np.ascontiguousarray(K[:-1]), np.ascontiguousarray(V[:-1]))
+        return lc
+
+    times, out, spent = [], None, 0.0
+    while spent < budget_s and len(times) < 50:
+        lc = fresh()
+        t0 = time.perf_counter()
+        out = lc.decode_step(k_new, v_new, step.q)
+        dt = time.perf_counter() - t0
+        times.append(dt)
+        spent += dt
+    best = min(times)
+    return {"value": cfg.num_jobs / best, "unit": "job-tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"whole {cfg.name} step (append + attention, {cfg.num_jobs} jobs, "
+                      f"{step.total_tokens} cached tokens), best of {len(times)} runs, "
+                      f"{spent:.1f}s of CPU work",
+            "seconds_per_step": best}, out
+
+
+def load_traffic(cfg_name):
+    """HBM bytes per attention launch measured with rocprofv3 --pmc (committed summary)."""
+    path = os.path.join(ROOT, "profiles", f"attn_partition_{cfg_name}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for ln in open(path):
+        if "=" in ln and not ln.lstrip().startswith("#"):
+            k, v = ln.split("=", 1)
+            vals[k.strip()] = v.strip()
+    try:
+        return float(vals["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--config", type=int, default=1, help="workload preset timed as the headline (default 1)")
+    ap.add_argument("--also", type=str, default="2,3", help="other presets reported under 'other_workloads'")
+    ap.add_argument("--footprint-gb", type=float, default=2.0, help="bytes touched between reuses of a replica")
+    ap.add_argument("--target-items", type=int, default=0)
+    ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by head with no exchange; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import fs_workload as wl
+    import paper_2305_05920_amd as fs
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    def log(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    pool_kw = {}
+    if args.target_items:
+        pool_kw["target_items"] = args.target_items
+
+    def measure(idx, steps, warmup, with_cpu):
+        cfg = wl.CONFIGS[idx]
+        reps = Replicas(fs, torch, wl, cfg, 0, args.footprint_gb * 1e9, pool_kw, log)
+        try:
+            if args.wgs_per_cu:
+                for p in reps.pools:
+                    p.set_param("wgs_per_cu", args.wgs_per_cu)
+            ms = time_steps(torch, reps, steps, warmup)
+            kt = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
+            res = {"workload": cfg.name, "ms_per_step": ms, "job_tokens_per_s": cfg.num_jobs / (ms / 1e3),
+                   "kernel_ms": kt, "alg_bytes": reps.alg_bytes, "replicas": reps.R,
+                   "attention_gbps": reps.alg_bytes / (kt["attention"] * 1e-3) / 1e9}
+            if not args.no_graph:
+                try:
+                    res["ms_per_step_graph"] = graph_ms(torch, reps, steps)
+                except Exception as e:  # graph capture is an extra, never the headline
+                    log(f"graph replay skipped: {e}")
+            # check the result of the last step against the oracle on the way
+            got = reps.out.cpu().numpy()
+            base = None
+            if with_cpu:
+                base, ref = cpu_baseline(reps)
+                diff = got.astype(np.float64) - ref
+                res["max_abs_err"] = float(np.abs(diff).max())
+                res["rel_l2_err"] = float(np.linalg.norm(diff) / np.linalg.norm(ref))
+            for p in reps.pools:
+                p.check()
+            log(json.dumps(res))
+            return res, base
+        finally:
+            reps.close()
+
+    main_res, base = measure(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
+    others = []
+    for tok in [t for t in args.also.split(",") if t.strip()]:
+        idx = int(tok)
+        if idx == args.config:
+            continue
+        r, _ = measure(idx, max(50, args.steps // 4), max(10, args.warmup // 4), False)
+        others.append(r)
+
+    cfg = wl.CONFIGS[args.config]
+    attn_ms = main_res["kernel_ms"]["attention"]
+    achieved = main_res["alg_bytes"] / (attn_ms * 1e-3) / 1e9
+    line = {
+        "metric": METRIC,
+        "value": main_res["job_tokens_per_s"],
+        "unit": "job-tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}: {cfg.num_jobs} jobs, {cfg.num_heads} heads x "
+                               f"{cfg.head_dim}, {cfg.dtype}, block 16, sum(L)={int(main_res['alg_bytes'] // (2 * cfg.num_heads * cfg.head_dim * cfg.elem_bytes))}",
+                   "step": "fs_kv_append + fs_decode_attention (partition pass + combine)",
+                   "pool_replicas": main_res["replicas"]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": load_traffic(cfg.name),
+                     "kernel": "fs_attn_partition_kernel", "kernel_ms": attn_ms,
+                     "alg_bytes_per_launch": main_res["alg_bytes"]},
+        "cpu_baseline": base,
+        "kernel_ms": main_res["kernel_ms"],
+        "ms_per_step_graph": main_res.get("ms_per_step_graph"),
+        "max_abs_err": main_res.get("max_abs_err"),
+        "rel_l2_err": main_res.get("rel_l2_err"),
+        "other_workloads": others,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,195 @@
+/*
+ * fastserve.h -- C ABI of the paged decode step for AMD MI355X (gfx950).
+ *
+ * One decode iteration of token-granularity preemptive serving (FastServe,
+ * arXiv 2305.05920): the scheduler admits a ragged batch of jobs (Section 3.2,
+ * Algorithm 1), the engine appends every job's new key/value token to that
+ * job's cache and runs the new token's masked self-attention over the whole
+ * cache (Section 2.2), and the cache manager moves blocks of inactive jobs
+ * between GPU memory and host memory (Section 4.2).
+ *
+ * Conventions
+ *   - Every function returns an fs_status (0 = FS_OK, negative = error) unless
+ *     noted.  No exception crosses this boundary.
+ *   - "device pointer" = HBM address valid on the pool's GPU; "host pointer" =
+ *     ordinary process memory.  The library never takes ownership of a pointer
+ *     it is given; the caller keeps q/k/v/out/tables/lengths alive until the
+ *     stream has run the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     that take a stream are asynchronous on it.
+ *   - A pool is not thread-safe; different pools may be used concurrently.
+ *     The pool's GPU must be the current device of the calling thread.
+ *   - The library never allocates or frees block ids: which block holds which
+ *     tokens is decided by the caller (the paper's key-value cache manager,
+ *     Section 3.2) and handed over as a block table.
+ *
+ * Pool layout (this library's choice; the paper fixes only block-grained
+ * allocation, Section 2.2).  With e = bytes per element, x = 16/e elements per
+ * 16-byte vector, B = block_size tokens, H = num_heads, D = head_dim, block b
+ * starts at byte b * fs_pool_block_bytes() and holds 2*H*B*D elements, the K
+ * region followed by the V region:
+ *     K[h][slot][d]  at element ((h*(D/x) + d/x)*B + slot)*x + d%x
+ *     V[h][slot][d]  at element H*B*D + (h*B + slot)*D + d
+ * so each (block, head) chunk of K or of V is B*D*e contiguous bytes (4 KiB at
+ * B=16, D=128, bf16), and one block is one contiguous copy for offload/upload.
+ * Logical token t of a job lives in block block_table[job][t / B], slot t % B.
+ */
+#ifndef FASTSERVE_H
+#define FASTSERVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fs_pool fs_pool; /* opaque; created and destroyed by the library */
+
+typedef enum fs_dtype {
+    FS_BF16 = 0, /* 2-byte bfloat16 pool, q, k, v                         */
+    FS_F32 = 1   /* 4-byte IEEE float pool, q, k, v                       */
+} fs_dtype;
+
+typedef enum fs_status {
+    FS_OK = 0,
+    FS_ERR_INVALID_ARG = -1, /* null pointer, negative count, size out of range       */
+    FS_ERR_OOM = -2,         /* device or pinned-host allocation failed               */
+    FS_ERR_BAD_TABLE = -3,   /* a kernel met a block id or length outside the pool    */
+    FS_ERR_HIP = -4,         /* a HIP runtime call failed                              */
+    FS_ERR_UNSUPPORTED = -5  /* dtype / head_dim / block_size combination not built   */
+} fs_status;
+
+typedef struct fs_pool_config {
+    int32_t dtype;           /* fs_dtype of pool, q, k, v                               */
+    int32_t num_heads;       /* heads resident on this GPU (key/value heads == query
+                                heads: the paper's models are multi-head, Table 1)     */
+    int32_t head_dim;        /* 64 or 128                                               */
+    int32_t block_size;      /* tokens per block; 16                                    */
+    int32_t num_blocks;      /* HBM blocks in the pool                                  */
+    int32_t num_host_blocks; /* pinned-host slots for offload; 0 = none                 */
+    int32_t max_jobs;        /* hint: largest num_jobs of one call (sizes scratch);
+                                0 = 1024.  Larger batches still work: they run in
+                                slices of this many jobs.                                */
+    int32_t target_items;    /* work items the attention kernel aims for; 0 = default  */
+    float scale;             /* softmax scale; 0 = 1/sqrt(head_dim)                     */
+    int32_t reserved;        /* must be 0                                               */
+    void *device_mem;        /* optional caller-owned HBM for the blocks (device
+                                pointer, 256-byte aligned); NULL = library allocates   */
+    size_t device_bytes;     /* size of device_mem; >= num_blocks * block bytes         */
+} fs_pool_config;
+
+/* ---- pool (Section 2.2 block-grained cache; Section 4.2 host extension) ---------- */
+
+/* Creates the block pool on the current device, its scratch buffers and, if
+ * num_host_blocks > 0, a pinned host mirror of that many block slots.
+ * Block contents start undefined.  *out is written only on FS_OK. */
+int fs_pool_create(const fs_pool_config *cfg, fs_pool **out);
+
+/* Synchronises the device and frees everything the library allocated. */
+int fs_pool_destroy(fs_pool *pool);
+
+/* Bytes of one block = 2*H*B*D*e.  Returns 0 for a NULL pool. */
+size_t fs_pool_block_bytes(const fs_pool *pool);
+
+/* Device pointer to block 0 (the caller's device_mem if one was given). */
+void *fs_pool_device_ptr(const fs_pool *pool);
+
+/* Synchronous copy of one whole block between host memory and the pool
+ * (test and harness helper; host pointer, fs_pool_block_bytes() bytes). */
+int fs_pool_write_block(fs_pool *pool, int32_t block_id, const void *host_src);
+int fs_pool_read_block(const fs_pool *pool, int32_t block_id, void *host_dst);
+
+/* Kernels never dereference a block id outside [0, num_blocks) or a position
+ * beyond table_stride*B: they skip it and raise a flag in device memory.
+ * fs_pool_check waits for `stream`, returns FS_ERR_BAD_TABLE if the flag was
+ * raised since the last check, and clears it. */
+int fs_pool_check(fs_pool *pool, void *stream);
+
+/* ---- KV append (Section 2.2, decoding phase: the new token's key and value join
+ *      the cache) ------------------------------------------------------------------
+ * For every job j: copies k[j], v[j] (device, [num_jobs][H][D], pool dtype) to
+ * logical position p = job_lens[j], i.e. block block_table[j*table_stride + p/B],
+ * slot p%B.  A bit copy: no conversion.
+ *   block_table: device int32 [num_jobs][table_stride]; entries beyond a job's
+ *                blocks are ignored.  The entry for p/B must already name a block
+ *                the caller allocated.
+ *   job_lens:    device int32 [num_jobs], tokens already cached (the write position).
+ * Two jobs must not append into the same (block, slot). */
+int fs_kv_append(fs_pool *pool, const int32_t *block_table, int32_t table_stride,
+                 const int32_t *job_lens, int32_t num_jobs, const void *k, const void *v,
+                 void *stream);
+
+/* ---- bulk KV write (Section 2.2, initialization phase: the first iteration builds
+ *      the cache of all prompt tokens) -----------------------------------------------
+ * Job j receives tokens [token_offsets[j], token_offsets[j+1]) of the packed
+ * arrays k, v (device, [total_tokens][H][D], pool dtype) at logical positions
+ * job_starts[j], job_starts[j]+1, ...
+ *   job_starts:    device int32 [num_jobs]
+ *   token_offsets: device int32 [num_jobs+1], non-decreasing, [0] = 0,
+ *                  [num_jobs] = total_tokens
+ *   total_tokens:  the same total, known to the host (sizes the launch). */
+int fs_kv_prefill(fs_pool *pool, const int32_t *block_table, int32_t table_stride,
+                  const int32_t *job_starts, const int32_t *token_offsets, int32_t num_jobs,
+                  int64_t total_tokens, const void *k, const void *v, void *stream);
+
+/* ---- decode attention (Section 2.2: masked self-attention of the one new token
+ *      over the keys and values of all tokens up to and including itself) ------------
+ * For every job j and head h, with L = job_lens[j] (tokens to attend over, i.e.
+ * the length after this step's append):
+ *     s_t = scale * <q[j][h], K_j[t][h]>,  w = softmax_t(s),  out[j][h] = sum_t w_t V_j[t][h]
+ *   q:   device [num_jobs][H][D], pool dtype
+ *   out: device float32 [num_jobs][H][D]; rows of a job with L == 0 are set to 0
+ *   max_len_hint: an upper bound of max_j job_lens[j] known to the host (sizes the
+ *                launch only; <= 0 means table_stride*B).  Lengths are read on the
+ *                device; the host is never synchronised.
+ * Uses the pool's scratch: two calls on one pool must not overlap in time. */
+int fs_decode_attention(const void *q, fs_pool *pool, const int32_t *block_table,
+                        int32_t table_stride, const int32_t *job_lens, int32_t num_jobs,
+                        int32_t max_len_hint, float *out, void *stream);
+
+/* ---- block offload / upload (Section 4.2: key-value tensors of inactive jobs are
+ *      swapped out to host memory and swapped in before the job is scheduled) --------
+ * Copies n whole blocks between pool blocks block_ids[i] and pinned host slots
+ * host_slots[i] (host int32 arrays, read before return), asynchronously on
+ * `stream`.  Upload may target any block id; the caller patches its tables. */
+int fs_pool_offload(fs_pool *pool, const int32_t *block_ids, const int32_t *host_slots,
+                    int32_t n, void *stream);
+int fs_pool_upload(fs_pool *pool, const int32_t *host_slots, const int32_t *block_ids,
+                   int32_t n, void *stream);
+
+/* ---- measurement and tuning helpers ---------------------------------------------- */
+
+typedef enum fs_kernel_kind {
+    FS_KERNEL_APPEND = 0,
+    FS_KERNEL_ATTENTION = 1, /* partitioned attention with online softmax             */
+    FS_KERNEL_COMBINE = 2,   /* merge of the partitions of one (job, head)            */
+    FS_KERNEL_PREFILL = 3,
+    FS_KERNEL_KINDS = 4
+} fs_kernel_kind;
+
+/* While enabled, every kernel launch is bracketed by HIP events on its stream. */
+int fs_profile_enable(fs_pool *pool, int32_t enable);
+/* Waits for the recorded events; adds up milliseconds and launch counts per
+ * fs_kernel_kind into total_ms[FS_KERNEL_KINDS], launches[FS_KERNEL_KINDS]
+ * (host arrays), then forgets the records. */
+int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
+
+/* Named integer knobs for sweeps: "target_items", "wgs_per_cu".  Unknown name or
+ * out-of-range value -> FS_ERR_INVALID_ARG. */
+int fs_pool_set_param(fs_pool *pool, const char *name, int32_t value);
+int fs_pool_get_param(const fs_pool *pool, const char *name, int32_t *value);
+
+/* Copies the attention kernel's last work plan to the host after waiting for
+ * `stream`: item_base[num_jobs+1] (prefix sum of partitions per job) and the
+ * partition size in 64-token steps.  Test helper. */
+int fs_pool_last_plan(fs_pool *pool, int32_t num_jobs, int32_t *item_base,
+                      int32_t *steps_per_partition, void *stream);
+
+const char *fs_strerror(int status);
+const char *fs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTSERVE_H */

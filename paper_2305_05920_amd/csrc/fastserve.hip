@@ -1,0 +1,1016 @@
+// Paged decode step for MI355X (gfx950): block pool, KV append, bulk KV write,
+// partitioned decode attention with online softmax, partition combine, block
+// offload/upload.  C ABI declared in include/fastserve.h.
+//
+// The operator is the masked self-attention of one new token per job over that
+// job's cached keys and values (FastServe, arXiv 2305.05920, Section 2.2); the
+// cache is allocated in blocks (Section 2.2) that can move between HBM and
+// host memory (Section 4.2).  Everything about how the work is laid out on the
+// GPU is this file's own design:
+//
+//  * One wavefront owns one work item = (job, head, partition of the sequence).
+//    A partition is a run of 64-token "steps"; in one step the 64 lanes score
+//    64 tokens (4 blocks x 16 slots), one token per lane, so q.k needs no
+//    cross-lane reduction: the K region of a block is stored [D/x][slot][x]
+//    (x elements = 16 bytes) and lane (row r, slot s) reads 16-byte vector i of
+//    token s of block 4k+r at chunk + (i*16 + s)*16 -- each load instruction
+//    covers four fully used 256-byte segments.
+//  * The V region is stored [slot][D]; in the value phase the wave walks the
+//    step's blocks one at a time, every load instruction covering 1 KiB of
+//    contiguous rows, and lane c accumulates dims [c*x, c*x+x) of the tokens it
+//    sees.  Softmax weights travel from the scoring lanes to the value lanes
+//    through 256 bytes of LDS per wave.
+//  * The work list is built inside the kernel from the device-resident lengths
+//    (prefix sum in LDS per workgroup), so the host never synchronises and the
+//    grid is persistent: every wave strides over the items.
+//  * The path is a batched GEMV at 1 flop/byte: HBM-bound, no MFMA.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "fastserve.h"
+
+namespace {
+
+constexpr int kBlockTokens = 16;       // tokens per pool block
+constexpr int kStepTokens = 64;        // tokens one wave scores per step
+constexpr int kStepBlocks = kStepTokens / kBlockTokens;
+constexpr int kWavesPerWg = 4;
+constexpr int kThreads = 64 * kWavesPerWg;
+constexpr int kJobsPerThread = 4;
+constexpr int kMaxJobsPerLaunch = kThreads * kJobsPerThread;  // 1024
+constexpr int kTableRefreshSteps = 64 / kStepBlocks;          // 64 table entries per refresh
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+struct BF16 { static constexpr int kBytes = 2; };
+struct F32 { static constexpr int kBytes = 4; };
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// dot of one 16-byte vector of K with the matching 16 bytes of q
+template <typename E>
+__device__ __forceinline__ float dot16(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
+                                       const uint32_t *q, float acc);
+template <>
+__device__ __forceinline__ float dot16<BF16>(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
+                                             const uint32_t *q, float acc) {
+    uint32_t q0 = q[0], q1 = q[1], q2 = q[2], q3 = q[3];
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k0), __builtin_bit_cast(bf16x2, q0), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k1), __builtin_bit_cast(bf16x2, q1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k2), __builtin_bit_cast(bf16x2, q2), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k3), __builtin_bit_cast(bf16x2, q3), acc, false);
+    return acc;
+}
+template <>
+__device__ __forceinline__ float dot16<F32>(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
+                                            const uint32_t *q, float acc) {
+    acc = fmaf(as_f32(k0), as_f32(q[0]), acc);
+    acc = fmaf(as_f32(k1), as_f32(q[1]), acc);
+    acc = fmaf(as_f32(k2), as_f32(q[2]), acc);
+    acc = fmaf(as_f32(k3), as_f32(q[3]), acc);
+    return acc;
+}
+
+// acc[0..x) += p * (one 16-byte vector of V)
+template <typename E>
+__device__ __forceinline__ void axpy16(float p, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, float *acc);
+template <>
+__device__ __forceinline__ void axpy16<BF16>(float p, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, float *acc) {
+    acc[0] = fmaf(p, as_f32(v0 << 16), acc[0]);
+    acc[1] = fmaf(p, as_f32(v0 & 0xffff0000u), acc[1]);
+    acc[2] = fmaf(p, as_f32(v1 << 16), acc[2]);
+    acc[3] = fmaf(p, as_f32(v1 & 0xffff0000u), acc[3]);
+    acc[4] = fmaf(p, as_f32(v2 << 16), acc[4]);
+    acc[5] = fmaf(p, as_f32(v2 & 0xffff0000u), acc[5]);
+    acc[6] = fmaf(p, as_f32(v3 << 16), acc[6]);
+    acc[7] = fmaf(p, as_f32(v3 & 0xffff0000u), acc[7]);
+}
+template <>
+__device__ __forceinline__ void axpy16<F32>(float p, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, float *acc) {
+    acc[0] = fmaf(p, as_f32(v0), acc[0]);
+    acc[1] = fmaf(p, as_f32(v1), acc[1]);
+    acc[2] = fmaf(p, as_f32(v2), acc[2]);
+    acc[3] = fmaf(p, as_f32(v3), acc[3]);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return as_f32((uint32_t)__builtin_amdgcn_update_dpp((int)as_u32(v), (int)as_u32(v), CTRL, 0xF, 0xF, false));
+}
+
+// maximum over the 64 lanes, returned wave-uniform
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_f32<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_f32<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_f32<0x141>(v));  // row_half_mirror
+    v = fmaxf(v, dpp_f32<0x140>(v));  // row_mirror: every lane of a 16-lane row holds the row max
+    float r0 = as_f32((uint32_t)__builtin_amdgcn_readlane((int)as_u32(v), 0));
+    float r1 = as_f32((uint32_t)__builtin_amdgcn_readlane((int)as_u32(v), 16));
+    float r2 = as_f32((uint32_t)__builtin_amdgcn_readlane((int)as_u32(v), 32));
+    float r3 = as_f32((uint32_t)__builtin_amdgcn_readlane((int)as_u32(v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// orders this wave's LDS writes before its later LDS reads (and the reverse)
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Partitioning rule shared by the attention and combine kernels: a job of
+// `steps` 64-token steps is cut into partitions of `chunk` steps each.
+__device__ __forceinline__ int chunk_of(int steps, int P) {
+    return steps > 0 ? ceil_div(steps, ceil_div(steps, P)) : 1;
+}
+
+struct AttnShape {
+    int32_t num_jobs;
+    int32_t num_heads;
+    int32_t table_stride;
+    int32_t num_blocks;
+    int32_t target_items;
+    int32_t items_cap;
+    float scale_log2e;
+};
+
+enum : int32_t { kErrBadBlock = 1, kErrBadLen = 2, kErrPlanOverflow = 4 };
+
+// ------------------------------------------------------------------------------------
+// Decode attention, partition pass.
+// plan[0..J]: prefix sum of partitions per job; plan[J+1]: steps per partition.
+// ------------------------------------------------------------------------------------
+template <typename E, int D>
+__global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
+    const uint32_t *__restrict__ q, const char *__restrict__ pool,
+    const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
+    float *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml,
+    int32_t *__restrict__ plan, int32_t *__restrict__ err, AttnShape sh)
+{
+    constexpr int X = 16 / E::kBytes;        // elements per 16-byte vector
+    constexpr int NK = D / X;                // 16-byte vectors per token row
+    constexpr int LPT = NK;                  // lanes per token row in the value phase
+    constexpr int TPI = 64 / LPT;            // token rows per value load instruction
+    constexpr int NV = kBlockTokens / TPI;   // value load instructions per block
+    constexpr int QW = NK * 4;               // 32-bit words of one q row
+    constexpr int kChunkBytes = kBlockTokens * D * E::kBytes;  // one (block, head) K or V chunk
+    static_assert(NK >= 2 && NK <= 32 && TPI * LPT == 64 && NV * TPI == kBlockTokens, "shape");
+
+    __shared__ int s_base[kMaxJobsPerLaunch + 1];
+    __shared__ int s_red[kWavesPerWg];
+    __shared__ int s_P;
+    __shared__ float s_p[kWavesPerWg][kStepTokens];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int J = sh.num_jobs, H = sh.num_heads;
+    const int max_len = sh.table_stride * kBlockTokens;
+    const size_t block_bytes = (size_t)2 * H * kChunkBytes;
+
+    // ---- work plan: steps per job, partition size, prefix sum of partitions ----
+    int st[kJobsPerThread];
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < kJobsPerThread; ++i) {
+        int j = tid * kJobsPerThread + i;
+        int L = j < J ? lens[j] : 0;
+        if (L < 0 || L > max_len) {
+            atomicOr(err, kErrBadLen);
+            L = L < 0 ? 0 : max_len;
+        }
+        st[i] = (L + kStepTokens - 1) / kStepTokens;
+        tot += st[i];
+    }
+    int wsum = tot;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) wsum += __shfl_xor(wsum, o);
+    if (lane == 0) s_red[wave] = wsum;
+    __syncthreads();
+    const long long total_steps = (long long)s_red[0] + s_red[1] + s_red[2] + s_red[3];
+    long long Pll = (total_steps * H + sh.target_items - 1) / sh.target_items;
+    const int P = Pll < 1 ? 1 : (Pll > (1 << 24) ? (1 << 24) : (int)Pll);
+    int nparts = 0;
+    int np[kJobsPerThread];
+#pragma unroll
+    for (int i = 0; i < kJobsPerThread; ++i) {
+        np[i] = st[i] > 0 ? ceil_div(st[i], chunk_of(st[i], P)) : 0;
+        nparts += np[i];
+    }
+    int incl = nparts;  // inclusive scan over the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    __syncthreads();  // s_red is reused
+    if (lane == 63) s_red[wave] = incl;
+    __syncthreads();
+    int wave_off = 0;
+    for (int w = 0; w < wave; ++w) wave_off += s_red[w];
+    int run = wave_off + incl - nparts;
+#pragma unroll
+    for (int i = 0; i < kJobsPerThread; ++i) {
+        int j = tid * kJobsPerThread + i;
+        if (j < J) s_base[j] = run;
+        run += np[i];
+    }
+    if (tid == kThreads - 1) {
+        // threads past the last job contribute 0, so this is the total
+        s_base[J] = run;
+        s_P = P;
+    }
+    __syncthreads();
+    int n_jp = s_base[J];
+    if ((long long)n_jp * H > sh.items_cap) {
+        // cannot happen for lengths inside the table (the scratch is sized for the
+        // bound target_items + J*H); refuse rather than write past the scratch
+        if (tid == 0) atomicOr(err, kErrPlanOverflow);
+        n_jp = 0;
+    }
+    if (blockIdx.x == 0) {
+        for (int j = tid; j <= J; j += kThreads) plan[j] = s_base[j];
+        if (tid == 0) plan[J + 1] = P;
+    }
+    const int n_items = n_jp * H;
+
+    const int r = lane >> 4;   // scoring: which of the step's 4 blocks
+    const int s = lane & 15;   //          which slot of that block
+    const int vt = lane / LPT; // value phase: token row inside a load instruction
+    const int vc = lane % LPT; //              16-byte column of the row
+    const int look_stride = (J + 64) >> 6;
+
+    for (int it = blockIdx.x * kWavesPerWg + wave; it < n_items; it += gridDim.x * kWavesPerWg) {
+        const int jp = it / H;
+        const int h = it - jp * H;
+        // ---- which job owns partition jp: 64-ary search of the prefix sums ----
+        int i1 = lane * look_stride;
+        i1 = i1 < J ? i1 : J;
+        const int c1 = __popcll(__ballot(s_base[i1] <= jp));
+        const int seg = (c1 - 1) * look_stride;
+        int i2 = seg + lane;
+        i2 = i2 < J ? i2 : J;
+        const int c2 = __popcll(__ballot(s_base[i2] <= jp));
+        const int j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
+        const int base_j = __builtin_amdgcn_readfirstlane(s_base[j]);
+        const int parts_j = __builtin_amdgcn_readfirstlane(s_base[j + 1]) - base_j;
+        const int part = jp - base_j;
+        int L = lens[j];
+        L = L < 0 ? 0 : (L > max_len ? max_len : L);
+        const int steps = (L + kStepTokens - 1) / kStepTokens;
+        const int chunk = chunk_of(steps, s_P);
+        const int k0 = part * chunk;
+        const int k1 = (k0 + chunk) < steps ? (k0 + chunk) : steps;
+        const int NB = (L + kBlockTokens - 1) / kBlockTokens;
+        const int32_t *trow = table + (size_t)j * sh.table_stride;
+
+        // q row of (j, h): wave-uniform, lives in scalar registers where it fits
+        uint32_t qw[QW];
+        {
+            const uint32_t *qrow = q + ((size_t)j * H + h) * QW;
+#pragma unroll
+            for (int i = 0; i < QW; ++i) qw[i] = qrow[i];
+        }
+        const size_t k_head_off = (size_t)h * kChunkBytes;
+        const size_t v_head_off = (size_t)H * kChunkBytes + (size_t)h * kChunkBytes;
+
+        float m_run = -INFINITY;
+        float l_lane = 0.f;
+        float acc[X];
+#pragma unroll
+        for (int i = 0; i < X; ++i) acc[i] = 0.f;
+
+        // table entries of 64 blocks at a time, one per lane
+        int kt = k0;
+        int tbl;
+        {
+            int e = kStepBlocks * kt + lane;
+            tbl = e < NB ? trow[e] : -1;
+        }
+        u32x4 kr[NK];
+        int bid_next;
+        auto issue_k = [&](int k) {
+            int bid = __shfl(tbl, kStepBlocks * (k - kt) + r);
+            bool ok = (kStepBlocks * k + r) < NB && (uint32_t)bid < (uint32_t)sh.num_blocks;
+            bid_next = ok ? bid : -1;
+            if (ok) {
+                const char *kp = pool + (size_t)bid * block_bytes + k_head_off + (size_t)s * 16;
+#pragma unroll
+                for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + (size_t)i * (kBlockTokens * 16));
+            } else {
+#pragma unroll
+                for (int i = 0; i < NK; ++i) kr[i] = u32x4{0u, 0u, 0u, 0u};
+            }
+        };
+        issue_k(k0);
+
+        for (int k = k0; k < k1; ++k) {
+            const int bid = bid_next;
+            // ---- scores of this step's 64 tokens ----
+            float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < NK; i += 2) {
+                d0 = dot16<E>(kr[i].x, kr[i].y, kr[i].z, kr[i].w, &qw[4 * i], d0);
+                d1 = dot16<E>(kr[i + 1].x, kr[i + 1].y, kr[i + 1].z, kr[i + 1].w, &qw[4 * i + 4], d1);
+            }
+            const int t = (kStepBlocks * k + r) * kBlockTokens + s;
+            const bool tok_ok = (t < L) && (bid >= 0);
+            const float sc = tok_ok ? (d0 + d1) * sh.scale_log2e : -INFINITY;
+            if ((kStepBlocks * k + r) < NB && bid < 0) atomicOr(err, kErrBadBlock);
+
+            // ---- value loads of this step's blocks ----
+            const int nbk = (NB - kStepBlocks * k) < kStepBlocks ? (NB - kStepBlocks * k) : kStepBlocks;
+            u32x4 vr[kStepBlocks][NV];
+            bool vok[kStepBlocks];
+#pragma unroll
+            for (int b = 0; b < kStepBlocks; ++b) {
+                const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
+                vok[b] = (b < nbk) && (bb >= 0);
+                if (vok[b]) {
+                    const char *vp = pool + (size_t)bb * block_bytes + v_head_off +
+                                     (size_t)vt * (D * E::kBytes) + (size_t)vc * 16;
+                    const int left = L - (kStepBlocks * k + b) * kBlockTokens;  // valid slots in this block
+                    if (left >= kBlockTokens) {
+#pragma unroll
+                        for (int i = 0; i < NV; ++i)
+                            vr[b][i] = *(const u32x4 *)(vp + (size_t)i * (TPI * D * E::kBytes));
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < NV; ++i) {
+                            if (i * TPI + vt < left)
+                                vr[b][i] = *(const u32x4 *)(vp + (size_t)i * (TPI * D * E::kBytes));
+                            else
+                                vr[b][i] = u32x4{0u, 0u, 0u, 0u};
+                        }
+                    }
+                }
+            }
+
+            // ---- next step's keys ----
+            if (k + 1 < k1) {
+                if (k + 1 - kt == kTableRefreshSteps) {
+                    kt = k + 1;
+                    int e = kStepBlocks * kt + lane;
+                    tbl = e < NB ? trow[e] : -1;
+                }
+                issue_k(k + 1);
+            }
+
+            // ---- online softmax (base 2; scale*log2(e) is folded into the scores) ----
+            const float m_step = wave_max(sc);
+            const float m_new = fmaxf(m_run, m_step);
+            if (m_new > m_run) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_lane *= alpha;
+#pragma unroll
+                for (int i = 0; i < X; ++i) acc[i] *= alpha;
+                m_run = m_new;
+            }
+            const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+            const float p = __builtin_amdgcn_exp2f(sc - m_ref);
+            l_lane += p;
+            s_p[wave][r * kBlockTokens + (s % TPI) * NV + (s / TPI)] = p;
+            wave_lds_sync();
+
+            // ---- out += p * V ----
+#pragma unroll
+            for (int b = 0; b < kStepBlocks; ++b) {
+                if (vok[b]) {
+                    float pv[NV];
+#pragma unroll
+                    for (int i = 0; i < NV; ++i) pv[i] = s_p[wave][b * kBlockTokens + vt * NV + i];
+#pragma unroll
+                    for (int i = 0; i < NV; ++i)
+                        axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
+                }
+            }
+            wave_lds_sync();
+        }
+
+        // ---- fold the TPI token-row classes and the per-lane sums ----
+#pragma unroll
+        for (int o = LPT; o < 64; o <<= 1) {
+#pragma unroll
+            for (int i = 0; i < X; ++i) acc[i] += __shfl_xor(acc[i], o);
+        }
+        float l_sum = l_lane;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) l_sum += __shfl_xor(l_sum, o);
+
+        if (lane < LPT) {
+            if (parts_j == 1) {
+                const float inv = l_sum > 0.f ? 1.f / l_sum : 0.f;
+                float *o = out + ((size_t)j * H + h) * D + (size_t)vc * X;
+#pragma unroll
+                for (int i = 0; i < X; ++i) o[i] = acc[i] * inv;
+            } else {
+                float *o = part_acc + (size_t)it * D + (size_t)vc * X;
+#pragma unroll
+                for (int i = 0; i < X; ++i) o[i] = acc[i];
+                if (lane == 0) {
+                    part_ml[(size_t)it * 2] = m_run;
+                    part_ml[(size_t)it * 2 + 1] = l_sum;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Combine: one wave per (job, head) merges that pair's partitions:
+//   M = max m_i, out = sum_i 2^(m_i-M) acc_i / sum_i 2^(m_i-M) l_i.
+// Jobs with one partition were written by the partition pass; jobs with no
+// tokens get zeros here.
+// ------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
+    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
+    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H)
+{
+    constexpr int PER = D / 64;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int jh = blockIdx.x * kWavesPerWg + wave;
+    if (jh >= J * H) return;
+    const int j = jh / H, h = jh - j * H;
+    const int base = plan[j];
+    const int n = plan[j + 1] - base;
+    float *o = out + (size_t)jh * D + lane * PER;
+    if (n == 1) return;
+    if (n == 0) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) o[i] = 0.f;
+        return;
+    }
+    float M = -INFINITY;
+    for (int p = 0; p < n; ++p) M = fmaxf(M, part_ml[((size_t)(base + p) * H + h) * 2]);
+    const float m_ref = (M == -INFINITY) ? 0.f : M;
+    float acc[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+    float l = 0.f;
+    for (int p = 0; p < n; ++p) {
+        const size_t it = (size_t)(base + p) * H + h;
+        const float w = __builtin_amdgcn_exp2f(part_ml[it * 2] - m_ref);
+        l = fmaf(w, part_ml[it * 2 + 1], l);
+        const float *a = part_acc + it * D + lane * PER;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) acc[i] = fmaf(w, a[i], acc[i]);
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) o[i] = acc[i] * inv;
+}
+
+// ------------------------------------------------------------------------------------
+// KV append: one thread moves one 16-byte vector of K and one of V.
+// ------------------------------------------------------------------------------------
+template <int EB>
+__global__ __launch_bounds__(kThreads) void fs_kv_append_kernel(
+    char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride,
+    const int32_t *__restrict__ lens, int32_t J, int32_t H, int32_t D, int32_t num_blocks,
+    const char *__restrict__ k, const char *__restrict__ v, int32_t *__restrict__ err)
+{
+    const int nk = D * EB / 16;  // vectors per (token, head) row
+    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= (long long)J * H * nk) return;
+    const int vec = (int)(idx % nk);
+    const long long jh = idx / nk;
+    const int h = (int)(jh % H);
+    const int j = (int)(jh / H);
+    const int pos = lens[j];
+    if (pos < 0 || pos / kBlockTokens >= table_stride) {
+        if (h == 0 && vec == 0) atomicOr(err, kErrBadLen);
+        return;
+    }
+    const int bid = table[(size_t)j * table_stride + pos / kBlockTokens];
+    if ((uint32_t)bid >= (uint32_t)num_blocks) {
+        if (h == 0 && vec == 0) atomicOr(err, kErrBadBlock);
+        return;
+    }
+    const int slot = pos % kBlockTokens;
+    const size_t chunk = (size_t)kBlockTokens * D * EB;
+    char *blk = pool + (size_t)bid * (2 * (size_t)H * chunk);
+    const size_t src = ((size_t)jh * nk + vec) * 16;
+    const u32x4 kv = *(const u32x4 *)(k + src);
+    const u32x4 vv = *(const u32x4 *)(v + src);
+    *(u32x4 *)(blk + (size_t)h * chunk + ((size_t)vec * kBlockTokens + slot) * 16) = kv;
+    *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
+}
+
+// ------------------------------------------------------------------------------------
+// Bulk KV write: one thread moves one 16-byte vector of K and one of V of one
+// packed token; the owning job is found by bisection of token_offsets.
+// ------------------------------------------------------------------------------------
+template <int EB>
+__global__ __launch_bounds__(kThreads) void fs_kv_prefill_kernel(
+    char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride,
+    const int32_t *__restrict__ starts, const int32_t *__restrict__ offs, int32_t J, int32_t H,
+    int32_t D, int32_t num_blocks, long long total_tokens, const char *__restrict__ k,
+    const char *__restrict__ v, int32_t *__restrict__ err)
+{
+    const int nk = D * EB / 16;
+    const long long per_tok = (long long)H * nk;
+    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total_tokens * per_tok) return;
+    const long long tok = idx / per_tok;
+    const int rem = (int)(idx - tok * per_tok);
+    const int h = rem / nk, vec = rem - h * nk;
+    int lo = 0, hi = J;  // last job with offs[job] <= tok
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if ((long long)offs[mid] <= tok) lo = mid; else hi = mid;
+    }
+    const int j = lo;
+    const long long in_job = tok - offs[j];
+    if (in_job < 0 || tok >= (long long)offs[j + 1]) {
+        if (rem == 0) atomicOr(err, kErrBadLen);
+        return;
+    }
+    const long long pos = (long long)starts[j] + in_job;
+    if (pos < 0 || pos / kBlockTokens >= table_stride) {
+        if (rem == 0) atomicOr(err, kErrBadLen);
+        return;
+    }
+    const int bid = table[(size_t)j * table_stride + pos / kBlockTokens];
+    if ((uint32_t)bid >= (uint32_t)num_blocks) {
+        if (rem == 0) atomicOr(err, kErrBadBlock);
+        return;
+    }
+    const int slot = (int)(pos % kBlockTokens);
+    const size_t chunk = (size_t)kBlockTokens * D * EB;
+    char *blk = pool + (size_t)bid * (2 * (size_t)H * chunk);
+    const size_t src = (size_t)idx * 16;
+    const u32x4 kv = *(const u32x4 *)(k + src);
+    const u32x4 vv = *(const u32x4 *)(v + src);
+    *(u32x4 *)(blk + (size_t)h * chunk + ((size_t)vec * kBlockTokens + slot) * 16) = kv;
+    *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
+}
+
+struct ProfileRecord {
+    int kind;
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct fs_pool {
+    fs_pool_config cfg;
+    int device = 0;
+    int num_cus = 256;
+    char *mem = nullptr;
+    bool owns_mem = false;
+    char *host_mem = nullptr;
+    size_t block_bytes = 0;
+    int elem_bytes = 2;
+    float scale = 0.f;
+    int max_jobs = 1024;
+    int target_items = 0;
+    int wgs_per_cu = 3;
+    int items_cap = 0;
+    float *part_acc = nullptr;
+    float *part_ml = nullptr;
+    int32_t *plan = nullptr;
+    int32_t *err = nullptr;
+    bool profiling = false;
+    std::vector<ProfileRecord> records;
+    std::vector<ProfileRecord> spare;
+};
+
+namespace {
+
+const char *kVersion = "fastserve-mi355x 0.1";
+
+bool on_pool_device(const fs_pool *p) {
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == p->device;
+}
+
+int alloc_scratch(fs_pool *p) {
+    const int H = p->cfg.num_heads, D = p->cfg.head_dim;
+    const int jobs = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
+    const long long cap = (long long)p->target_items + (long long)jobs * H;
+    if (cap > (1LL << 30)) return FS_ERR_INVALID_ARG;
+    float *acc = nullptr, *ml = nullptr;
+    if (hipMalloc((void **)&acc, (size_t)cap * D * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
+    if (hipMalloc((void **)&ml, (size_t)cap * 2 * sizeof(float)) != hipSuccess) {
+        (void)hipFree(acc);
+        return FS_ERR_OOM;
+    }
+    if (p->part_acc) (void)hipFree(p->part_acc);
+    if (p->part_ml) (void)hipFree(p->part_ml);
+    p->part_acc = acc;
+    p->part_ml = ml;
+    p->items_cap = (int)cap;
+    return FS_OK;
+}
+
+struct ProfileScope {
+    fs_pool *p;
+    hipStream_t s;
+    ProfileRecord rec{};
+    bool on;
+    ProfileScope(fs_pool *pool, int kind, hipStream_t stream) : p(pool), s(stream), on(pool->profiling) {
+        if (!on) return;
+        if (!p->spare.empty()) {
+            rec = p->spare.back();
+            p->spare.pop_back();
+        } else if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) {
+            on = false;
+            return;
+        }
+        rec.kind = kind;
+        (void)hipEventRecord(rec.start, s);
+    }
+    ~ProfileScope() {
+        if (!on) return;
+        (void)hipEventRecord(rec.stop, s);
+        p->records.push_back(rec);
+    }
+};
+
+template <typename E, int D>
+int launch_attention(fs_pool *p, const void *q, const int32_t *table, int32_t stride,
+                     const int32_t *lens, int32_t J, int32_t max_len, float *out, hipStream_t s)
+{
+    AttnShape sh;
+    sh.num_jobs = J;
+    sh.num_heads = p->cfg.num_heads;
+    sh.table_stride = stride;
+    sh.num_blocks = p->cfg.num_blocks;
+    sh.target_items = p->target_items;
+    sh.items_cap = p->items_cap;
+    sh.scale_log2e = p->scale * 1.4426950408889634f;
+    const long long steps_bound = (long long)ceil_div(max_len, kStepTokens);
+    long long items_bound = (long long)J * sh.num_heads * steps_bound;
+    long long wgs = (items_bound + kWavesPerWg - 1) / kWavesPerWg;
+    const long long persistent = (long long)p->num_cus * p->wgs_per_cu;
+    if (wgs > persistent) wgs = persistent;
+    if (wgs < 1) wgs = 1;
+    {
+        ProfileScope ps(p, FS_KERNEL_ATTENTION, s);
+        hipLaunchKernelGGL((fs_attn_partition_kernel<E, D>), dim3((unsigned)wgs), dim3(kThreads), 0, s,
+                           (const uint32_t *)q, (const char *)p->mem, table, lens, out, p->part_acc,
+                           p->part_ml, p->plan, p->err, sh);
+    }
+    if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
+    {
+        ProfileScope ps(p, FS_KERNEL_COMBINE, s);
+        const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
+        hipLaunchKernelGGL((fs_attn_combine_kernel<D>), dim3((unsigned)cw), dim3(kThreads), 0, s,
+                           (const float *)p->part_acc, (const float *)p->part_ml,
+                           (const int32_t *)p->plan, out, J, sh.num_heads);
+    }
+    if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
+    return FS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
+{
+    if (!cfg || !out) return FS_ERR_INVALID_ARG;
+    if (cfg->dtype != FS_BF16 && cfg->dtype != FS_F32) return FS_ERR_UNSUPPORTED;
+    if (cfg->head_dim != 64 && cfg->head_dim != 128) return FS_ERR_UNSUPPORTED;
+    if (cfg->block_size != kBlockTokens) return FS_ERR_UNSUPPORTED;
+    if (cfg->num_heads <= 0 || cfg->num_heads > 65535 || cfg->num_blocks <= 0 || cfg->num_host_blocks < 0 ||
+        cfg->max_jobs < 0 || cfg->target_items < 0 || cfg->reserved != 0 || !(cfg->scale >= 0.f) ||
+        !std::isfinite(cfg->scale))
+        return FS_ERR_INVALID_ARG;
+    fs_pool *p = new (std::nothrow) fs_pool();
+    if (!p) return FS_ERR_OOM;
+    p->cfg = *cfg;
+    p->elem_bytes = cfg->dtype == FS_BF16 ? 2 : 4;
+    p->block_bytes = (size_t)2 * cfg->num_heads * kBlockTokens * cfg->head_dim * p->elem_bytes;
+    p->scale = cfg->scale > 0.f ? cfg->scale : (float)(1.0 / std::sqrt((double)cfg->head_dim));
+    p->max_jobs = cfg->max_jobs > 0 ? cfg->max_jobs : 1024;
+    int rc = FS_OK;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&p->device) != hipSuccess || hipGetDeviceProperties(&prop, p->device) != hipSuccess) {
+        delete p;
+        return FS_ERR_HIP;
+    }
+    p->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    p->target_items = cfg->target_items > 0 ? cfg->target_items
+                                            : p->num_cus * p->wgs_per_cu * kWavesPerWg * 4;
+    const size_t need = p->block_bytes * (size_t)cfg->num_blocks;
+    if (cfg->device_mem) {
+        if (cfg->device_bytes < need || ((uintptr_t)cfg->device_mem & 255u)) {
+            delete p;
+            return FS_ERR_INVALID_ARG;
+        }
+        p->mem = (char *)cfg->device_mem;
+    } else {
+        if (hipMalloc((void **)&p->mem, need) != hipSuccess) {
+            (void)hipGetLastError();
+            delete p;
+            return FS_ERR_OOM;
+        }
+        p->owns_mem = true;
+    }
+    if (cfg->num_host_blocks > 0 &&
+        hipHostMalloc((void **)&p->host_mem, p->block_bytes * (size_t)cfg->num_host_blocks, hipHostMallocDefault) !=
+            hipSuccess) {
+        (void)hipGetLastError();
+        rc = FS_ERR_OOM;
+    }
+    if (rc == FS_OK) rc = alloc_scratch(p);
+    if (rc == FS_OK && hipMalloc((void **)&p->plan, (kMaxJobsPerLaunch + 2) * sizeof(int32_t)) != hipSuccess)
+        rc = FS_ERR_OOM;
+    if (rc == FS_OK && hipMalloc((void **)&p->err, 256) != hipSuccess) rc = FS_ERR_OOM;
+    if (rc == FS_OK && (hipMemset(p->err, 0, 256) != hipSuccess ||
+                        hipMemset(p->plan, 0, (kMaxJobsPerLaunch + 2) * sizeof(int32_t)) != hipSuccess))
+        rc = FS_ERR_HIP;
+    if (rc != FS_OK) {
+        (void)hipGetLastError();
+        fs_pool_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return FS_OK;
+}
+
+int fs_pool_destroy(fs_pool *p)
+{
+    if (!p) return FS_ERR_INVALID_ARG;
+    (void)hipDeviceSynchronize();
+    for (auto &r : p->records) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    for (auto &r : p->spare) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    if (p->owns_mem && p->mem) (void)hipFree(p->mem);
+    if (p->host_mem) (void)hipHostFree(p->host_mem);
+    if (p->part_acc) (void)hipFree(p->part_acc);
+    if (p->part_ml) (void)hipFree(p->part_ml);
+    if (p->plan) (void)hipFree(p->plan);
+    if (p->err) (void)hipFree(p->err);
+    delete p;
+    return FS_OK;
+}
+
+size_t fs_pool_block_bytes(const fs_pool *p) { return p ? p->block_bytes : 0; }
+
+void *fs_pool_device_ptr(const fs_pool *p) { return p ? (void *)p->mem : nullptr; }
+
+int fs_pool_write_block(fs_pool *p, int32_t block_id, const void *host_src)
+{
+    if (!p || !host_src || block_id < 0 || block_id >= p->cfg.num_blocks) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    if (hipMemcpy(p->mem + (size_t)block_id * p->block_bytes, host_src, p->block_bytes, hipMemcpyHostToDevice) !=
+        hipSuccess)
+        return FS_ERR_HIP;
+    return FS_OK;
+}
+
+int fs_pool_read_block(const fs_pool *p, int32_t block_id, void *host_dst)
+{
+    if (!p || !host_dst || block_id < 0 || block_id >= p->cfg.num_blocks) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    if (hipMemcpy(host_dst, p->mem + (size_t)block_id * p->block_bytes, p->block_bytes, hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return FS_ERR_HIP;
+    return FS_OK;
+}
+
+int fs_pool_check(fs_pool *p, void *stream)
+{
+    if (!p) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t flag = 0;
+    if (hipMemcpyAsync(&flag, p->err, sizeof flag, hipMemcpyDeviceToHost, s) != hipSuccess) return FS_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return FS_ERR_HIP;
+    if (flag) {
+        if (hipMemsetAsync(p->err, 0, sizeof flag, s) != hipSuccess) return FS_ERR_HIP;
+        if (hipStreamSynchronize(s) != hipSuccess) return FS_ERR_HIP;
+        return FS_ERR_BAD_TABLE;
+    }
+    return FS_OK;
+}
+
+int fs_kv_append(fs_pool *p, const int32_t *table, int32_t stride, const int32_t *lens, int32_t J,
+                 const void *k, const void *v, void *stream)
+{
+    if (!p || J < 0) return FS_ERR_INVALID_ARG;
+    if (J == 0) return FS_OK;
+    if (!table || !lens || !k || !v || stride <= 0) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int H = p->cfg.num_heads, D = p->cfg.head_dim;
+    const long long vecs = (long long)J * H * (D * p->elem_bytes / 16);
+    const long long wgs = (vecs + kThreads - 1) / kThreads;
+    if (wgs > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    {
+        ProfileScope ps(p, FS_KERNEL_APPEND, s);
+        if (p->elem_bytes == 2)
+            hipLaunchKernelGGL((fs_kv_append_kernel<2>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
+                               stride, lens, J, H, D, p->cfg.num_blocks, (const char *)k, (const char *)v, p->err);
+        else
+            hipLaunchKernelGGL((fs_kv_append_kernel<4>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
+                               stride, lens, J, H, D, p->cfg.num_blocks, (const char *)k, (const char *)v, p->err);
+    }
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_t *starts,
+                  const int32_t *offs, int32_t J, int64_t total_tokens, const void *k, const void *v, void *stream)
+{
+    if (!p || J < 0 || total_tokens < 0) return FS_ERR_INVALID_ARG;
+    if (J == 0 || total_tokens == 0) return FS_OK;
+    if (!table || !starts || !offs || !k || !v || stride <= 0) return FS_ERR_INVALID_ARG;
+    if (total_tokens > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int H = p->cfg.num_heads, D = p->cfg.head_dim;
+    const long long vecs = (long long)total_tokens * H * (D * p->elem_bytes / 16);
+    const long long wgs = (vecs + kThreads - 1) / kThreads;
+    if (wgs > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    {
+        ProfileScope ps(p, FS_KERNEL_PREFILL, s);
+        if (p->elem_bytes == 2)
+            hipLaunchKernelGGL((fs_kv_prefill_kernel<2>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
+                               stride, starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens,
+                               (const char *)k, (const char *)v, p->err);
+        else
+            hipLaunchKernelGGL((fs_kv_prefill_kernel<4>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
+                               stride, starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens,
+                               (const char *)k, (const char *)v, p->err);
+    }
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+int fs_decode_attention(const void *q, fs_pool *p, const int32_t *table, int32_t stride,
+                        const int32_t *lens, int32_t J, int32_t max_len_hint, float *out, void *stream)
+{
+    if (!p || J < 0) return FS_ERR_INVALID_ARG;
+    if (J == 0) return FS_OK;
+    if (!q || !table || !lens || !out || stride <= 0) return FS_ERR_INVALID_ARG;
+    if ((long long)stride * kBlockTokens > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int H = p->cfg.num_heads, D = p->cfg.head_dim;
+    int max_len = stride * kBlockTokens;
+    if (max_len_hint > 0 && max_len_hint < max_len) max_len = max_len_hint;
+    const int slice = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
+    const size_t row_bytes = (size_t)H * D * p->elem_bytes;
+    for (int j0 = 0; j0 < J; j0 += slice) {
+        const int n = (J - j0) < slice ? (J - j0) : slice;
+        const void *qs = (const char *)q + (size_t)j0 * row_bytes;
+        const int32_t *ts = table + (size_t)j0 * stride;
+        float *os = out + (size_t)j0 * H * D;
+        int rc;
+        if (p->cfg.dtype == FS_BF16)
+            rc = D == 128 ? launch_attention<BF16, 128>(p, qs, ts, stride, lens + j0, n, max_len, os, s)
+                          : launch_attention<BF16, 64>(p, qs, ts, stride, lens + j0, n, max_len, os, s);
+        else
+            rc = D == 128 ? launch_attention<F32, 128>(p, qs, ts, stride, lens + j0, n, max_len, os, s)
+                          : launch_attention<F32, 64>(p, qs, ts, stride, lens + j0, n, max_len, os, s);
+        if (rc != FS_OK) return rc;
+    }
+    return FS_OK;
+}
+
+static int copy_blocks(fs_pool *p, const int32_t *block_ids, const int32_t *host_slots, int32_t n, void *stream,
+                       bool to_host)
+{
+    if (!p || n < 0) return FS_ERR_INVALID_ARG;
+    if (n == 0) return FS_OK;
+    if (!block_ids || !host_slots || !p->host_mem) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i)
+        if (block_ids[i] < 0 || block_ids[i] >= p->cfg.num_blocks || host_slots[i] < 0 ||
+            host_slots[i] >= p->cfg.num_host_blocks)
+            return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    // runs of consecutive (block id, host slot) pairs travel as one copy
+    int i = 0;
+    while (i < n) {
+        int run = 1;
+        while (i + run < n && block_ids[i + run] == block_ids[i] + run && host_slots[i + run] == host_slots[i] + run)
+            ++run;
+        char *dev = p->mem + (size_t)block_ids[i] * p->block_bytes;
+        char *host = p->host_mem + (size_t)host_slots[i] * p->block_bytes;
+        hipError_t e = to_host ? hipMemcpyAsync(host, dev, p->block_bytes * run, hipMemcpyDeviceToHost, s)
+                               : hipMemcpyAsync(dev, host, p->block_bytes * run, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return FS_ERR_HIP;
+        i += run;
+    }
+    return FS_OK;
+}
+
+int fs_pool_offload(fs_pool *p, const int32_t *block_ids, const int32_t *host_slots, int32_t n, void *stream)
+{
+    return copy_blocks(p, block_ids, host_slots, n, stream, true);
+}
+
+int fs_pool_upload(fs_pool *p, const int32_t *host_slots, const int32_t *block_ids, int32_t n, void *stream)
+{
+    return copy_blocks(p, block_ids, host_slots, n, stream, false);
+}
+
+int fs_profile_enable(fs_pool *p, int32_t enable)
+{
+    if (!p) return FS_ERR_INVALID_ARG;
+    p->profiling = enable != 0;
+    return FS_OK;
+}
+
+int fs_profile_collect(fs_pool *p, float *total_ms, int32_t *launches)
+{
+    if (!p || !total_ms || !launches) return FS_ERR_INVALID_ARG;
+    for (int i = 0; i < FS_KERNEL_KINDS; ++i) {
+        total_ms[i] = 0.f;
+        launches[i] = 0;
+    }
+    int rc = FS_OK;
+    for (auto &r : p->records) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+            rc = FS_ERR_HIP;
+        else if (r.kind >= 0 && r.kind < FS_KERNEL_KINDS) {
+            total_ms[r.kind] += ms;
+            launches[r.kind] += 1;
+        }
+        p->spare.push_back(r);
+    }
+    p->records.clear();
+    return rc;
+}
+
+int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
+{
+    if (!p || !name) return FS_ERR_INVALID_ARG;
+    if (!std::strcmp(name, "target_items")) {
+        if (value < 1 || value > (1 << 24)) return FS_ERR_INVALID_ARG;
+        if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+        if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
+        const int old = p->target_items;
+        p->target_items = value;
+        int rc = alloc_scratch(p);
+        if (rc != FS_OK) p->target_items = old;
+        return rc;
+    }
+    if (!std::strcmp(name, "wgs_per_cu")) {
+        if (value < 1 || value > 8) return FS_ERR_INVALID_ARG;
+        p->wgs_per_cu = value;
+        return FS_OK;
+    }
+    return FS_ERR_INVALID_ARG;
+}
+
+int fs_pool_get_param(const fs_pool *p, const char *name, int32_t *value)
+{
+    if (!p || !name || !value) return FS_ERR_INVALID_ARG;
+    if (!std::strcmp(name, "target_items")) *value = p->target_items;
+    else if (!std::strcmp(name, "wgs_per_cu")) *value = p->wgs_per_cu;
+    else if (!std::strcmp(name, "num_cus")) *value = p->num_cus;
+    else if (!std::strcmp(name, "items_cap")) *value = p->items_cap;
+    else if (!std::strcmp(name, "max_jobs_per_launch")) *value = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
+    else return FS_ERR_INVALID_ARG;
+    return FS_OK;
+}
+
+int fs_pool_last_plan(fs_pool *p, int32_t J, int32_t *item_base, int32_t *steps_per_partition, void *stream)
+{
+    if (!p || !item_base || !steps_per_partition || J < 0 || J > kMaxJobsPerLaunch) return FS_ERR_INVALID_ARG;
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipStreamSynchronize(s) != hipSuccess) return FS_ERR_HIP;
+    if (hipMemcpy(item_base, p->plan, (size_t)(J + 1) * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return FS_ERR_HIP;
+    if (hipMemcpy(steps_per_partition, p->plan + J + 1, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return FS_ERR_HIP;
+    return FS_OK;
+}
+
+const char *fs_strerror(int status)
+{
+    switch (status) {
+    case FS_OK: return "ok";
+    case FS_ERR_INVALID_ARG: return "invalid argument";
+    case FS_ERR_OOM: return "out of memory";
+    case FS_ERR_BAD_TABLE: return "block table or length outside the pool";
+    case FS_ERR_HIP: return "HIP runtime error";
+    case FS_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or block_size";
+    default: return "unknown status";
+    }
+}
+
+const char *fs_version(void) { return kVersion; }
+
+}  // extern "C"

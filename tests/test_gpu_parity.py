@@ -1,0 +1,316 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle
+(attention, to the benchmark spec's tolerance) and the layout model (placement, bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+import fs_workload as wl
+import oracle
+from tests import harness as hs
+
+pytestmark = pytest.mark.gpu
+
+
+def run_full_step(case, fill="image", prefix_image=None, **pool_kw):
+    run = hs.DeviceRun(case, fill=fill, prefix_image=prefix_image, **pool_kw)
+    try:
+        run.append()
+        got = run.attention(max_len_hint=int(case.step.lens.max(initial=0)))
+        run.pool.check()
+        img = run.image()
+    finally:
+        run.close()
+    return got, img
+
+
+# ---- whole step on the five workload presets -------------------------------------
+@pytest.mark.parametrize("idx,rep", [(0, 0), (0, 1), (0, 2), (1, 0), (1, 1), (1, 2), (2, 0), (2, 1), (2, 2),
+                                     (3, 0), (3, 1), (3, 2)])
+def test_step_matches_oracle_and_layout(idx, rep):
+    cfg = wl.CONFIGS[idx]
+    print(f"[case] preset {cfg.name} rep {rep}", flush=True)
+    case = hs.make_case(cfg, rep)
+    bt = case.step.tables
+    if rep == 0:
+        # pool filled from the layout model's image; the whole pool is compared after the append
+        want_img = hs.expected_image(case, bt.table, bt.num_blocks, upto="prefix")
+        got, img = run_full_step(case, fill="image", prefix_image=want_img)
+        hs.append_into(want_img, case, bt.table)
+        assert np.array_equal(img.view(np.uint8), want_img.view(np.uint8)), "pool image differs from the layout model"
+    else:
+        # pool filled by the bulk-write kernel; the appended cells are read back through the model
+        got, img = run_full_step(case, fill="prefill")
+        lay = hs.layout_of(cfg)
+        for j in range(cfg.num_jobs):
+            k1, v1 = lay.read_tokens(img, bt.table[j], int(case.lens_before[j]), 1)
+            assert np.array_equal(k1[0], case.k_new[j]) and np.array_equal(v1[0], case.v_new[j])
+    hs.assert_parity(got, hs.oracle_step(case), f"{cfg.name} rep {rep}")
+
+
+@pytest.mark.parametrize("rep", [0, 1, 2])
+def test_long_context_reduced_job_count(rep):
+    # preset 4 with 2 of its 8 jobs at a quarter of the length: same heads, same
+    # kernels, several partitions per job and the combine kernel, oracle in seconds
+    cfg = wl.CONFIGS[4].scaled(num_jobs=2, max_len=8192, num_heads=16)
+    print(f"[case] long context reduced rep {rep}", flush=True)
+    case = hs.make_case(cfg, rep)
+    got, img = run_full_step(case, fill="prefill", target_items=512)
+    want_img = hs.expected_image(case, case.step.tables.table, case.step.tables.num_blocks)
+    assert np.array_equal(img.view(np.uint8), want_img.view(np.uint8))
+    hs.assert_parity(got, hs.oracle_step(case), f"long_context reduced rep {rep}")
+
+
+# ---- placement alone ---------------------------------------------------------------
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_prefill_then_append_is_bit_exact_and_touches_nothing_else(idx):
+    cfg = wl.CONFIGS[idx].scaled(num_jobs=min(wl.CONFIGS[idx].num_jobs, 24))
+    case = hs.make_case(cfg, 1)
+    run = hs.DeviceRun(case, fill="prefill")
+    try:
+        after_prefill = run.image()
+        want = hs.expected_image(case, run.table_np, run.num_blocks, upto="prefix")
+        assert np.array_equal(after_prefill.view(np.uint8), want.view(np.uint8))
+        run.append()
+        run.pool.check()
+        want = hs.expected_image(case, run.table_np, run.num_blocks, upto="append")
+        assert np.array_equal(run.image().view(np.uint8), want.view(np.uint8))
+    finally:
+        run.close()
+
+
+def test_append_copies_any_bit_pattern():
+    # NaN and infinity patterns included: the append is a copy, not arithmetic
+    cfg = wl.CONFIGS[1].scaled(num_jobs=5, num_heads=3)
+    case = hs.make_case(cfg, 0, lens=[1, 16, 17, 33, 100])
+    rng = np.random.default_rng(5)
+    case.k_new = rng.integers(0, 65536, size=case.k_new.shape).astype(np.uint16)
+    case.v_new = rng.integers(0, 65536, size=case.v_new.shape).astype(np.uint16)
+    for j, (K, V) in enumerate(case.caches):
+        K[-1], V[-1] = case.k_new[j], case.v_new[j]
+    run = hs.DeviceRun(case, fill="image")
+    try:
+        run.append()
+        run.pool.check()
+        want = hs.expected_image(case, run.table_np, run.num_blocks)
+        assert np.array_equal(run.image(), want)
+    finally:
+        run.close()
+
+
+# ---- edge cases of the attention kernels -------------------------------------------
+EDGE_LENS = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1000]
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_block_and_step_boundaries(dtype, D):
+    cfg = wl.CONFIGS[1].scaled(num_jobs=len(EDGE_LENS), num_heads=5, head_dim=D, dtype=dtype, max_len=1024)
+    case = hs.make_case(cfg, 0, lens=EDGE_LENS)
+    got, _ = run_full_step(case)
+    ref = hs.oracle_step(case)
+    hs.assert_parity(got, ref, f"edges {dtype} D={D}")
+    # a one-token cache returns its value row exactly
+    v0 = wl.to_f64(dtype, case.caches[0][1][0])
+    assert np.array_equal(got[0].astype(np.float64), v0)
+
+
+@pytest.mark.parametrize("target", [1, 7, 64, 100000])
+def test_partition_sizes_do_not_change_the_result(target):
+    # target_items steers how many 64-token steps one partition holds: from one
+    # partition per job (no combine) to one step per partition (long combine)
+    cfg = wl.CONFIGS[3].scaled(num_jobs=9, num_heads=4)
+    case = hs.make_case(cfg, 2, lens=[64, 65, 640, 641, 2048, 2047, 1, 1537, 300])
+    got, _ = run_full_step(case, target_items=target)
+    hs.assert_parity(got, hs.oracle_step(case), f"target_items={target}")
+
+
+def test_partition_plan_covers_every_step_once():
+    cfg = wl.CONFIGS[3].scaled(num_jobs=9, num_heads=4)
+    lens = np.array([64, 65, 640, 641, 2048, 2047, 1, 1537, 300], dtype=np.int32)
+    case = hs.make_case(cfg, 2, lens=lens)
+    run = hs.DeviceRun(case, target_items=64)
+    try:
+        run.append()
+        run.attention()
+        base, P = run.pool.last_plan(cfg.num_jobs)
+        steps = (lens + 63) // 64
+        total = int(steps.sum())
+        assert P == max(1, -(-total * cfg.num_heads // 64))
+        parts = np.diff(base)
+        for n, s in zip(parts, steps):
+            chunk = -(-s // (-(-s // P)))
+            assert n == -(-s // chunk) and (n - 1) * chunk < s <= n * chunk
+        assert base[0] == 0 and base[-1] * cfg.num_heads <= run.pool.get_param("items_cap")
+    finally:
+        run.close()
+
+
+def test_empty_jobs_give_zero_rows():
+    cfg = wl.CONFIGS[1].scaled(num_jobs=4, num_heads=3)
+    case = hs.make_case(cfg, 0, lens=[0, 40, 0, 7])
+    import paper_2305_05920_amd as fs
+    img = hs.expected_image(case, case.step.tables.table, case.step.tables.num_blocks, upto="append")
+    mem = hs.to_torch(cfg.dtype, img)
+    with fs.Pool(cfg.dtype, cfg.num_heads, cfg.head_dim, case.step.tables.num_blocks, device_mem=mem) as pool:
+        out = torch.full((4, 3, 128), float("nan"), dtype=torch.float32, device="cuda")
+        fs.fs_decode_attention(hs.to_torch(cfg.dtype, case.step.q), pool,
+                               torch.from_numpy(case.step.tables.table).cuda(),
+                               torch.from_numpy(case.step.lens).cuda(), out)
+        pool.check()
+        got = out.cpu().numpy()
+    assert not got[0].any() and not got[2].any()
+    hs.assert_parity(got, hs.oracle_step(case), "empty jobs")
+
+
+def test_all_jobs_empty():
+    import paper_2305_05920_amd as fs
+    with fs.Pool("bf16", 2, 128, 4) as pool:
+        out = torch.full((3, 2, 128), float("nan"), dtype=torch.float32, device="cuda")
+        q = torch.zeros((3, 2, 128), dtype=torch.bfloat16, device="cuda")
+        table = torch.full((3, 2), -1, dtype=torch.int32, device="cuda")
+        fs.fs_decode_attention(q, pool, table, torch.zeros(3, dtype=torch.int32, device="cuda"), out)
+        pool.check()
+        assert not out.cpu().numpy().any()
+        # zero jobs: a no-op that must not launch anything
+        fs.fs_decode_attention(q[:0], pool, table[:0], torch.zeros(0, dtype=torch.int32, device="cuda"), out[:0])
+        fs.fs_kv_append(pool, table[:0], torch.zeros(0, dtype=torch.int32, device="cuda"), q[:0], q[:0])
+
+
+def test_same_job_twice_in_a_batch_gives_identical_rows():
+    # two table rows naming the same blocks (shared prefix read by two queries)
+    cfg = wl.CONFIGS[1].scaled(num_jobs=2, num_heads=4)
+    case = hs.make_case(cfg, 0, lens=[333, 50])
+    import paper_2305_05920_amd as fs
+    bt = case.step.tables
+    img = hs.expected_image(case, bt.table, bt.num_blocks, upto="append")
+    table = np.stack([bt.table[0], bt.table[1], bt.table[0]])
+    lens = np.array([333, 50, 333], dtype=np.int32)
+    q = np.stack([case.step.q[0], case.step.q[1], case.step.q[0]])
+    with fs.Pool(cfg.dtype, 4, 128, bt.num_blocks, device_mem=hs.to_torch("bf16", img)) as pool:
+        out = torch.empty((3, 4, 128), dtype=torch.float32, device="cuda")
+        fs.fs_decode_attention(hs.to_torch("bf16", q), pool, torch.from_numpy(table).cuda(),
+                               torch.from_numpy(lens).cuda(), out)
+        pool.check()
+        got = out.cpu().numpy()
+    assert np.array_equal(got[0], got[2])
+    hs.assert_parity(got[:2], hs.oracle_step(case), "duplicate job")
+
+
+def test_more_jobs_than_one_launch_slice():
+    # max_jobs=8 forces three slices of the batch through the same scratch
+    cfg = wl.CONFIGS[2].scaled(num_jobs=20, num_heads=3)
+    case = hs.make_case(cfg, 0)
+    got, _ = run_full_step(case, max_jobs=8, target_items=16)
+    hs.assert_parity(got, hs.oracle_step(case), "sliced batch")
+
+
+def test_widest_table_of_the_long_context_preset():
+    # W = 2048 table entries per job, one job at the full 32768 tokens, 2 heads
+    cfg = wl.CONFIGS[4].scaled(num_jobs=1, num_heads=2)
+    case = hs.make_case(cfg, 0, lens=[32768])
+    assert case.step.tables.table.shape[1] == 2048
+    got, _ = run_full_step(case, fill="prefill")
+    hs.assert_parity(got, hs.oracle_step(case), "max length")
+
+
+# ---- offload / upload ----------------------------------------------------------------
+def test_offload_upload_round_trip_and_bitwise_stable_attention():
+    # preset 2's recipe: a quarter of the jobs leave for host slots and return under
+    # other block ids.  Blocks must arrive bit-exact, and since the work split depends
+    # on lengths only, attention must be bitwise the same before and after.
+    cfg = wl.CONFIGS[2].scaled(num_jobs=64)
+    case = hs.make_case(cfg, 0)
+    bt = case.step.tables
+    sw = bt.swap
+    import paper_2305_05920_amd as fs
+    run = hs.DeviceRun(case, fill="image", table=bt.table_before_swap, num_host_blocks=len(sw.old_ids))
+    try:
+        run.append()
+        before = run.attention()
+        img_before = run.image().copy()
+        fs.fs_pool_offload(run.pool, sw.old_ids, sw.host_slots)
+        torch.cuda.synchronize()
+        # scribble over the vacated blocks so that a stale read would show
+        view = run.mem.view(torch.int16) if cfg.dtype == "bf16" else run.mem
+        view[torch.from_numpy(sw.old_ids.astype(np.int64)).cuda()] = 0x7FC1 if cfg.dtype == "bf16" else -1.0
+        fs.fs_pool_upload(run.pool, sw.host_slots, sw.new_ids)
+        torch.cuda.synchronize()
+        img_after = run.image()
+        assert np.array_equal(img_after[sw.new_ids], img_before[sw.old_ids])
+        run.table = torch.from_numpy(bt.table).cuda()
+        after = run.attention()
+        run.pool.check()
+        assert np.array_equal(before.view(np.uint32), after.view(np.uint32))
+        hs.assert_parity(after, hs.oracle_step(case), "after swap")
+    finally:
+        run.close()
+
+
+# ---- errors are reported, not faulted on -----------------------------------------------
+def test_bad_tables_and_lengths_raise_the_flag():
+    import paper_2305_05920_amd as fs
+    cfg = wl.CONFIGS[1].scaled(num_jobs=3, num_heads=2)
+    case = hs.make_case(cfg, 0, lens=[20, 40, 60])
+    run = hs.DeviceRun(case)
+    try:
+        run.append()
+        run.attention()
+        run.pool.check()
+        bad = run.table.clone()
+        bad[1, 0] = run.num_blocks + 5                    # block id beyond the pool
+        fs.fs_decode_attention(run.q, run.pool, bad, run.lens, run.out)
+        with pytest.raises(fs.FsError) as e:
+            run.pool.check()
+        assert e.value.status == fs.FS_ERR_BAD_TABLE
+        run.pool.check()                                  # flag was cleared
+        bad[1, 0] = -1
+        fs.fs_kv_append(run.pool, bad, torch.zeros(3, dtype=torch.int32, device="cuda"), run.k_new, run.v_new)
+        with pytest.raises(fs.FsError):
+            run.pool.check()
+        too_long = torch.tensor([20, 10 ** 6, 60], dtype=torch.int32, device="cuda")
+        fs.fs_decode_attention(run.q, run.pool, run.table, too_long, run.out)
+        with pytest.raises(fs.FsError):
+            run.pool.check()
+        fs.fs_kv_append(run.pool, run.table, too_long, run.k_new, run.v_new)
+        with pytest.raises(fs.FsError):
+            run.pool.check()
+        # host-checkable mistakes are refused before any launch
+        with pytest.raises(fs.FsError) as e:
+            fs.fs_pool_offload(run.pool, [0], [0])        # pool has no host slots
+        assert e.value.status == fs.FS_ERR_INVALID_ARG
+        with pytest.raises(fs.FsError):
+            run.pool.write_block(run.num_blocks, np.zeros(run.pool.block_bytes, np.uint8))
+    finally:
+        run.close()
+
+
+def test_library_allocated_pool_and_raw_block_copies():
+    import paper_2305_05920_amd as fs
+    with fs.Pool("f32", 2, 64, 6, num_host_blocks=2) as pool:
+        assert pool.block_bytes == 2 * 2 * 16 * 64 * 4
+        rng = np.random.default_rng(0)
+        a = rng.standard_normal(pool.block_bytes // 4).astype(np.float32)
+        pool.write_block(3, a)
+        assert np.array_equal(pool.read_block(3, np.float32), a)
+        fs.fs_pool_offload(pool, [3], [1])
+        fs.fs_pool_upload(pool, [1], [5])
+        torch.cuda.synchronize()
+        assert np.array_equal(pool.read_block(5, np.float32), a)
+
+
+def test_kernel_timing_records():
+    cfg = wl.CONFIGS[0]
+    case = hs.make_case(cfg, 0)
+    run = hs.DeviceRun(case)
+    try:
+        run.pool.profile_enable(True)
+        run.append()
+        run.attention()
+        run.attention()
+        rec = run.pool.profile_collect()
+        assert rec["append"]["launches"] == 1 and rec["attention"]["launches"] == 2
+        assert rec["combine"]["launches"] == 2 and rec["attention"]["ms"] > 0
+        run.pool.profile_enable(False)
+        run.attention()
+        assert run.pool.profile_collect()["attention"]["launches"] == 0
+    finally:
+        run.close()
