@@ -214,7 +214,6 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload preset timed as the headline (default 1)")
     ap.add_argument("--also", type=str, default="2,3", help="other presets reported under 'other_workloads'")
     ap.add_argument("--footprint-gb", type=float, default=2.0, help="bytes touched between reuses of a replica")
-    ap.add_argument("--target-items", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -236,8 +235,6 @@ def main():
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
     pool_kw = {}
-    if args.target_items:
-        pool_kw["target_items"] = args.target_items
 
     def measure(idx, steps, warmup, with_cpu):
         cfg = wl.CONFIGS[idx]

@@ -71,7 +71,7 @@ typedef struct fs_pool_config {
     int32_t max_jobs;        /* hint: largest num_jobs of one call (sizes scratch);
                                 0 = 1024.  Larger batches still work: they run in
                                 slices of this many jobs.                                */
-    int32_t target_items;    /* work items the attention kernel aims for; 0 = default  */
+    int32_t max_workgroups;  /* cap on the attention grid in workgroups; 0 = none       */
     float scale;             /* softmax scale; 0 = 1/sqrt(head_dim)                     */
     int32_t reserved;        /* must be 0                                               */
     void *device_mem;        /* optional caller-owned HBM for the blocks (device
@@ -175,16 +175,26 @@ int fs_profile_enable(fs_pool *pool, int32_t enable);
  * (host arrays), then forgets the records. */
 int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
 
-/* Named integer knobs for sweeps: "target_items", "wgs_per_cu".  Unknown name or
- * out-of-range value -> FS_ERR_INVALID_ARG. */
+/* Named integer knobs for sweeps: "wgs_per_cu" (persistent attention workgroups per
+ * compute unit, 1..8) and "max_workgroups" (cap on that grid, 0 = none); readable
+ * also: "num_cus", "max_jobs_per_launch".  Unknown name or out-of-range value ->
+ * FS_ERR_INVALID_ARG. */
 int fs_pool_set_param(fs_pool *pool, const char *name, int32_t value);
 int fs_pool_get_param(const fs_pool *pool, const char *name, int32_t *value);
 
 /* Copies the attention kernel's last work plan to the host after waiting for
- * `stream`: item_base[num_jobs+1] (prefix sum of partitions per job) and the
- * partition size in 64-token steps.  Test helper. */
-int fs_pool_last_plan(fs_pool *pool, int32_t num_jobs, int32_t *item_base,
-                      int32_t *steps_per_partition, void *stream);
+ * `stream`: step_base[num_jobs+1], the prefix sum over jobs of 64-token steps
+ * (ceil(job_lens[j] / 64)) that the kernels split evenly over the waves.  Test
+ * helper; num_jobs at most 1024 (the last launch slice of a larger batch). */
+int fs_pool_last_plan(fs_pool *pool, int32_t num_jobs, int32_t *step_base, void *stream);
+
+/* Plain streaming kernels of known size (not part of the decode path): a read of
+ * `bytes` from src and a copy of `bytes` from src to dst, device pointers, 16-byte
+ * aligned, bytes a multiple of 16, on `workgroups` workgroups of 256 threads.  They
+ * give the practical HBM ceiling of the GPU at hand and the scale of the hardware
+ * byte counters.  sink: 16 writable device bytes. */
+int fs_stream_read(const void *src, size_t bytes, void *sink, int32_t workgroups, void *stream);
+int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups, void *stream);
 
 const char *fs_strerror(int status);
 const char *fs_version(void);

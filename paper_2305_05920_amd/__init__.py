@@ -15,7 +15,7 @@ from typing import Optional
 import torch  # first: the library binds to the HIP runtime torch has loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfastserve.so")
+LIB_PATH = os.environ.get("FS_LIBRARY") or os.path.join(_HERE, "libfastserve.so")
 
 FS_BF16, FS_F32 = 0, 1
 FS_OK = 0
@@ -27,7 +27,7 @@ EXPORTS = (
     "fs_pool_write_block", "fs_pool_read_block", "fs_pool_check", "fs_kv_append", "fs_kv_prefill",
     "fs_decode_attention", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
     "fs_profile_collect", "fs_pool_set_param", "fs_pool_get_param", "fs_pool_last_plan",
-    "fs_strerror", "fs_version",
+    "fs_stream_read", "fs_stream_copy", "fs_strerror", "fs_version",
 )
 
 
@@ -42,7 +42,7 @@ class fs_pool_config(ctypes.Structure):
         ("dtype", ctypes.c_int32), ("num_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
         ("num_host_blocks", ctypes.c_int32), ("max_jobs", ctypes.c_int32),
-        ("target_items", ctypes.c_int32), ("scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("max_workgroups", ctypes.c_int32), ("scale", ctypes.c_float), ("reserved", ctypes.c_int32),
         ("device_mem", ctypes.c_void_p), ("device_bytes", ctypes.c_size_t),
     ]
 
@@ -80,7 +80,9 @@ def load_library() -> ctypes.CDLL:
     lib.fs_profile_collect.argtypes = [vp, P(ctypes.c_float), P(i32)]
     lib.fs_pool_set_param.argtypes = [vp, ctypes.c_char_p, i32]
     lib.fs_pool_get_param.argtypes = [vp, ctypes.c_char_p, P(i32)]
-    lib.fs_pool_last_plan.argtypes = [vp, i32, vp, P(i32), vp]
+    lib.fs_pool_last_plan.argtypes = [vp, i32, vp, vp]
+    lib.fs_stream_read.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
+    lib.fs_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, i32, vp]
     lib.fs_strerror.argtypes = [ctypes.c_int]
     lib.fs_strerror.restype = ctypes.c_char_p
     lib.fs_version.restype = ctypes.c_char_p
@@ -136,7 +138,7 @@ class Pool:
 
     def __init__(self, dtype: str, num_heads: int, head_dim: int, num_blocks: int,
                  block_size: int = 16, num_host_blocks: int = 0, max_jobs: int = 0,
-                 target_items: int = 0, scale: float = 0.0,
+                 max_workgroups: int = 0, scale: float = 0.0,
                  device_mem: Optional[torch.Tensor] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the decode path runs on the GPU only")
@@ -149,7 +151,7 @@ class Pool:
         cfg.dtype = {"bf16": FS_BF16, "f32": FS_F32}[dtype]
         cfg.num_heads, cfg.head_dim, cfg.block_size = num_heads, head_dim, block_size
         cfg.num_blocks, cfg.num_host_blocks = num_blocks, num_host_blocks
-        cfg.max_jobs, cfg.target_items, cfg.scale, cfg.reserved = max_jobs, target_items, scale, 0
+        cfg.max_jobs, cfg.max_workgroups, cfg.scale, cfg.reserved = max_jobs, max_workgroups, scale, 0
         self._device_mem = device_mem          # keep the caller's tensor alive
         if device_mem is not None:
             cfg.device_mem = _dev(device_mem, "device_mem")
@@ -225,10 +227,9 @@ class Pool:
     def last_plan(self, num_jobs: int, stream=None):
         import numpy as np
         base = np.zeros(num_jobs + 1, dtype=np.int32)
-        steps = ctypes.c_int32()
-        _ok(self._lib.fs_pool_last_plan(self._h, int(num_jobs), base.ctypes.data, ctypes.byref(steps),
-                                        _stream_ptr(stream)), "fs_pool_last_plan")
-        return base, steps.value
+        _ok(self._lib.fs_pool_last_plan(self._h, int(num_jobs), base.ctypes.data, _stream_ptr(stream)),
+            "fs_pool_last_plan")
+        return base
 
 
 def fs_pool_create(**kw) -> Pool:
@@ -297,3 +298,18 @@ def fs_pool_upload(pool: Pool, host_slots, block_ids, stream=None) -> None:
         raise ValueError("block_ids and host_slots differ in length")
     _ok(pool._lib.fs_pool_upload(pool._h, s.ctypes.data, b.ctypes.data, len(b), _stream_ptr(stream)),
         "fs_pool_upload")
+
+
+def fs_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int, stream=None) -> None:
+    """Reads every byte of `src` once (measurement helper)."""
+    _ok(load_library().fs_stream_read(_dev(src, "src"), src.numel() * src.element_size(), _dev(sink, "sink"),
+                                      int(workgroups), _stream_ptr(stream)), "fs_stream_read")
+
+
+def fs_stream_copy(dst: torch.Tensor, src: torch.Tensor, workgroups: int, stream=None) -> None:
+    """Copies `src` to `dst` with a plain kernel (measurement helper)."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < n:
+        raise ValueError("dst smaller than src")
+    _ok(load_library().fs_stream_copy(_dev(dst, "dst"), _dev(src, "src"), n, int(workgroups),
+                                      _stream_ptr(stream)), "fs_stream_copy")

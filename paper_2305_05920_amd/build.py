@@ -27,8 +27,8 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    tmp = LIB + f".tmp{os.getpid()}"
+def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    tmp = out + f".tmp{os.getpid()}"
     cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, SRC, "-o", tmp,
            "-Wl,-rpath,/opt/rocm/lib"]
     if verbose:
@@ -40,8 +40,8 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

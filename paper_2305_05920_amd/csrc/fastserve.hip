@@ -30,9 +30,17 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "fastserve.h"
+
+// Experiments may pin the attention kernel's register budget: -DFS_ATTN_WAVES_PER_EU=n
+#ifdef FS_ATTN_WAVES_PER_EU
+#define FS_ATTN_OCCUPANCY_ATTR __attribute__((amdgpu_waves_per_eu(FS_ATTN_WAVES_PER_EU, FS_ATTN_WAVES_PER_EU)))
+#else
+#define FS_ATTN_OCCUPANCY_ATTR
+#endif
 
 namespace {
 
@@ -127,30 +135,36 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 __host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Partitioning rule shared by the attention and combine kernels: a job of
-// `steps` 64-token steps is cut into partitions of `chunk` steps each.
-__device__ __forceinline__ int chunk_of(int steps, int P) {
-    return steps > 0 ? ceil_div(steps, ceil_div(steps, P)) : 1;
-}
-
 struct AttnShape {
     int32_t num_jobs;
     int32_t num_heads;
     int32_t table_stride;
     int32_t num_blocks;
-    int32_t target_items;
-    int32_t items_cap;
     float scale_log2e;
 };
 
-enum : int32_t { kErrBadBlock = 1, kErrBadLen = 2, kErrPlanOverflow = 4 };
+enum : int32_t { kErrBadBlock = 1, kErrBadLen = 2 };
+
+// Work split shared by the partition pass and the combine pass.  The batch is one
+// flat sequence of S = H * sum_j steps_j units, ordered [job][head][step], a unit
+// being one 64-token step of one (job, head).  Wave w of nw owns the units
+// [w*S/nw, (w+1)*S/nw): every wave gets the same amount of work whatever the mix of
+// job lengths, and the split depends on the lengths only, never on block ids.
+__device__ __forceinline__ long long range_lo(long long w, long long S, long long nw) { return w * S / nw; }
+// the wave that owns unit u
+__device__ __forceinline__ long long wave_of_unit(long long u, long long S, long long nw) {
+    return ((u + 1) * nw + S - 1) / S - 1;
+}
 
 // ------------------------------------------------------------------------------------
 // Decode attention, partition pass.
-// plan[0..J]: prefix sum of partitions per job; plan[J+1]: steps per partition.
+//   plan[0..J]: prefix sum of 64-token steps per job (written for the combine pass)
+//   A (job, head) whose steps all fall into one wave's range is finished here; one
+//   that is cut by a range boundary leaves a partial (m, l, acc) per wave involved:
+//   slot 0 of the wave if the pair began before the wave's range, else slot 1.
 // ------------------------------------------------------------------------------------
 template <typename E, int D>
-__global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
+__global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_partition_kernel(
     const uint32_t *__restrict__ q, const char *__restrict__ pool,
     const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
     float *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml,
@@ -162,12 +176,12 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
     constexpr int TPI = 64 / LPT;            // token rows per value load instruction
     constexpr int NV = kBlockTokens / TPI;   // value load instructions per block
     constexpr int QW = NK * 4;               // 32-bit words of one q row
-    constexpr int kChunkBytes = kBlockTokens * D * E::kBytes;  // one (block, head) K or V chunk
+    constexpr int kRowBytes = D * E::kBytes;
+    constexpr int kChunkBytes = kBlockTokens * kRowBytes;  // one (block, head) K or V chunk
     static_assert(NK >= 2 && NK <= 32 && TPI * LPT == 64 && NV * TPI == kBlockTokens, "shape");
 
     __shared__ int s_base[kMaxJobsPerLaunch + 1];
     __shared__ int s_red[kWavesPerWg];
-    __shared__ int s_P;
     __shared__ float s_p[kWavesPerWg][kStepTokens];
 
     const int tid = threadIdx.x;
@@ -177,99 +191,91 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
     const int max_len = sh.table_stride * kBlockTokens;
     const size_t block_bytes = (size_t)2 * H * kChunkBytes;
 
-    // ---- work plan: steps per job, partition size, prefix sum of partitions ----
+    // ---- prefix sum of steps per job, in LDS ----
     int st[kJobsPerThread];
     int tot = 0;
+    {
+        int Lr[kJobsPerThread];
 #pragma unroll
-    for (int i = 0; i < kJobsPerThread; ++i) {
-        int j = tid * kJobsPerThread + i;
-        int L = j < J ? lens[j] : 0;
-        if (L < 0 || L > max_len) {
-            atomicOr(err, kErrBadLen);
-            L = L < 0 ? 0 : max_len;
+        for (int i = 0; i < kJobsPerThread; ++i) {
+            const int j = tid * kJobsPerThread + i;
+            Lr[i] = j < J ? lens[j] : 0;
         }
-        st[i] = (L + kStepTokens - 1) / kStepTokens;
-        tot += st[i];
-    }
-    int wsum = tot;
+        bool bad = false;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) wsum += __shfl_xor(wsum, o);
-    if (lane == 0) s_red[wave] = wsum;
-    __syncthreads();
-    const long long total_steps = (long long)s_red[0] + s_red[1] + s_red[2] + s_red[3];
-    long long Pll = (total_steps * H + sh.target_items - 1) / sh.target_items;
-    const int P = Pll < 1 ? 1 : (Pll > (1 << 24) ? (1 << 24) : (int)Pll);
-    int nparts = 0;
-    int np[kJobsPerThread];
-#pragma unroll
-    for (int i = 0; i < kJobsPerThread; ++i) {
-        np[i] = st[i] > 0 ? ceil_div(st[i], chunk_of(st[i], P)) : 0;
-        nparts += np[i];
+        for (int i = 0; i < kJobsPerThread; ++i) {
+            int L = Lr[i];
+            bad |= (L < 0) | (L > max_len);
+            L = L < 0 ? 0 : (L > max_len ? max_len : L);
+            st[i] = (L + kStepTokens - 1) / kStepTokens;
+            tot += st[i];
+        }
+        if (bad) atomicOr(err, kErrBadLen);
     }
-    int incl = nparts;  // inclusive scan over the wave
+    int incl = tot;  // inclusive scan over the wave
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
         int up = __shfl_up(incl, o);
         if (lane >= o) incl += up;
     }
-    __syncthreads();  // s_red is reused
     if (lane == 63) s_red[wave] = incl;
     __syncthreads();
-    int wave_off = 0;
-    for (int w = 0; w < wave; ++w) wave_off += s_red[w];
-    int run = wave_off + incl - nparts;
+    int run = incl - tot;
+    for (int w = 0; w < wave; ++w) run += s_red[w];
 #pragma unroll
     for (int i = 0; i < kJobsPerThread; ++i) {
-        int j = tid * kJobsPerThread + i;
+        const int j = tid * kJobsPerThread + i;
         if (j < J) s_base[j] = run;
-        run += np[i];
+        run += st[i];
     }
-    if (tid == kThreads - 1) {
-        // threads past the last job contribute 0, so this is the total
-        s_base[J] = run;
-        s_P = P;
-    }
+    if (tid == kThreads - 1) s_base[J] = run;  // threads past the last job add 0: the total
     __syncthreads();
-    int n_jp = s_base[J];
-    if ((long long)n_jp * H > sh.items_cap) {
-        // cannot happen for lengths inside the table (the scratch is sized for the
-        // bound target_items + J*H); refuse rather than write past the scratch
-        if (tid == 0) atomicOr(err, kErrPlanOverflow);
-        n_jp = 0;
-    }
-    if (blockIdx.x == 0) {
+    if (blockIdx.x == 0)
         for (int j = tid; j <= J; j += kThreads) plan[j] = s_base[j];
-        if (tid == 0) plan[J + 1] = P;
-    }
-    const int n_items = n_jp * H;
+
+    // ---- this wave's range of units ----
+    const long long S = (long long)__builtin_amdgcn_readfirstlane(s_base[J]) * H;
+    const long long nw = (long long)gridDim.x * kWavesPerWg;
+    const long long gw = (long long)blockIdx.x * kWavesPerWg + wave;
+    const long long lo = range_lo(gw, S, nw);
+    const long long hi = range_lo(gw + 1, S, nw);
+    if (lo >= hi) return;
 
     const int r = lane >> 4;   // scoring: which of the step's 4 blocks
     const int s = lane & 15;   //          which slot of that block
     const int vt = lane / LPT; // value phase: token row inside a load instruction
     const int vc = lane % LPT; //              16-byte column of the row
-    const int look_stride = (J + 64) >> 6;
+    float *const p_wr = &s_p[wave][r * kBlockTokens + (s % TPI) * NV + (s / TPI)];
+    const float *const p_rd = &s_p[wave][vt * NV];
 
-    for (int it = blockIdx.x * kWavesPerWg + wave; it < n_items; it += gridDim.x * kWavesPerWg) {
-        const int jp = it / H;
-        const int h = it - jp * H;
-        // ---- which job owns partition jp: 64-ary search of the prefix sums ----
+    // ---- the job that owns unit lo: 64-ary search of the prefix sums ----
+    int j;
+    {
+        const int key = (int)(lo / H);  // s_base[j]*H <= lo  <=>  s_base[j] <= lo / H
+        const int look_stride = (J + 64) >> 6;
         int i1 = lane * look_stride;
         i1 = i1 < J ? i1 : J;
-        const int c1 = __popcll(__ballot(s_base[i1] <= jp));
+        const int c1 = __popcll(__ballot(s_base[i1] <= key));
         const int seg = (c1 - 1) * look_stride;
         int i2 = seg + lane;
         i2 = i2 < J ? i2 : J;
-        const int c2 = __popcll(__ballot(s_base[i2] <= jp));
-        const int j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
-        const int base_j = __builtin_amdgcn_readfirstlane(s_base[j]);
-        const int parts_j = __builtin_amdgcn_readfirstlane(s_base[j + 1]) - base_j;
-        const int part = jp - base_j;
-        int L = lens[j];
-        L = L < 0 ? 0 : (L > max_len ? max_len : L);
-        const int steps = (L + kStepTokens - 1) / kStepTokens;
-        const int chunk = chunk_of(steps, s_P);
-        const int k0 = part * chunk;
-        const int k1 = (k0 + chunk) < steps ? (k0 + chunk) : steps;
+        const int c2 = __popcll(__ballot(s_base[i2] <= key));
+        j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
+    }
+    int L = lens[j];
+    L = L < 0 ? 0 : (L > max_len ? max_len : L);
+    int steps = (L + kStepTokens - 1) / kStepTokens;
+    int h, k0;
+    {
+        const int local = (int)(lo - (long long)__builtin_amdgcn_readfirstlane(s_base[j]) * H);
+        h = local / steps;
+        k0 = local - h * steps;
+    }
+
+    for (long long u = lo; u < hi;) {
+        const long long room = hi - u;
+        const int k1 = (long long)(steps - k0) <= room ? steps : k0 + (int)room;
+        const int kf = k1 < (L / kStepTokens) ? k1 : (L / kStepTokens);  // steps [k0, kf) hold 64 valid tokens
         const int NB = (L + kBlockTokens - 1) / kBlockTokens;
         const int32_t *trow = table + (size_t)j * sh.table_stride;
 
@@ -280,8 +286,9 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
 #pragma unroll
             for (int i = 0; i < QW; ++i) qw[i] = qrow[i];
         }
-        const size_t k_head_off = (size_t)h * kChunkBytes;
-        const size_t v_head_off = (size_t)H * kChunkBytes + (size_t)h * kChunkBytes;
+        const char *const k_head = pool + (size_t)h * kChunkBytes + (size_t)s * 16;
+        const char *const v_head = pool + (size_t)H * kChunkBytes + (size_t)h * kChunkBytes +
+                                   (size_t)vt * kRowBytes + (size_t)vc * 16;
 
         float m_run = -INFINITY;
         float l_lane = 0.f;
@@ -289,83 +296,41 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
 #pragma unroll
         for (int i = 0; i < X; ++i) acc[i] = 0.f;
 
-        // table entries of 64 blocks at a time, one per lane
+        // table entries of 64 blocks at a time, one per lane, fetched one window ahead
         int kt = k0;
-        int tbl;
+        int tbl, tbl_next;
         {
             int e = kStepBlocks * kt + lane;
             tbl = e < NB ? trow[e] : -1;
+            e += 64;
+            tbl_next = e < NB ? trow[e] : -1;
         }
-        u32x4 kr[NK];
-        int bid_next;
-        auto issue_k = [&](int k) {
-            int bid = __shfl(tbl, kStepBlocks * (k - kt) + r);
-            bool ok = (kStepBlocks * k + r) < NB && (uint32_t)bid < (uint32_t)sh.num_blocks;
-            bid_next = ok ? bid : -1;
-            if (ok) {
-                const char *kp = pool + (size_t)bid * block_bytes + k_head_off + (size_t)s * 16;
-#pragma unroll
-                for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + (size_t)i * (kBlockTokens * 16));
-            } else {
-#pragma unroll
-                for (int i = 0; i < NK; ++i) kr[i] = u32x4{0u, 0u, 0u, 0u};
+        // table entry of block 4k+r (this lane's scoring row); -1 past the job's blocks
+        auto row_block = [&](int k) -> int {
+            if (k - kt == kTableRefreshSteps) {
+                kt = k;
+                tbl = tbl_next;
+                int e = kStepBlocks * kt + 64 + lane;
+                tbl_next = e < NB ? trow[e] : -1;
             }
+            return __shfl(tbl, kStepBlocks * (k - kt) + r);
         };
-        issue_k(k0);
-
-        for (int k = k0; k < k1; ++k) {
-            const int bid = bid_next;
-            // ---- scores of this step's 64 tokens ----
-            float d0 = 0.f, d1 = 0.f;
-#pragma unroll
-            for (int i = 0; i < NK; i += 2) {
-                d0 = dot16<E>(kr[i].x, kr[i].y, kr[i].z, kr[i].w, &qw[4 * i], d0);
-                d1 = dot16<E>(kr[i + 1].x, kr[i + 1].y, kr[i + 1].z, kr[i + 1].w, &qw[4 * i + 4], d1);
+        auto flag_bad = [&](int bid) -> int {
+            // a block id outside the pool is never dereferenced: block 0 is read in its
+            // place and the error flag is raised (the output of that job is then void)
+            if ((uint32_t)bid >= (uint32_t)sh.num_blocks) {
+                atomicOr(err, kErrBadBlock);
+                return 0;
             }
-            const int t = (kStepBlocks * k + r) * kBlockTokens + s;
-            const bool tok_ok = (t < L) && (bid >= 0);
-            const float sc = tok_ok ? (d0 + d1) * sh.scale_log2e : -INFINITY;
-            if ((kStepBlocks * k + r) < NB && bid < 0) atomicOr(err, kErrBadBlock);
+            return bid;
+        };
 
-            // ---- value loads of this step's blocks ----
-            const int nbk = (NB - kStepBlocks * k) < kStepBlocks ? (NB - kStepBlocks * k) : kStepBlocks;
-            u32x4 vr[kStepBlocks][NV];
-            bool vok[kStepBlocks];
-#pragma unroll
-            for (int b = 0; b < kStepBlocks; ++b) {
-                const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
-                vok[b] = (b < nbk) && (bb >= 0);
-                if (vok[b]) {
-                    const char *vp = pool + (size_t)bb * block_bytes + v_head_off +
-                                     (size_t)vt * (D * E::kBytes) + (size_t)vc * 16;
-                    const int left = L - (kStepBlocks * k + b) * kBlockTokens;  // valid slots in this block
-                    if (left >= kBlockTokens) {
-#pragma unroll
-                        for (int i = 0; i < NV; ++i)
-                            vr[b][i] = *(const u32x4 *)(vp + (size_t)i * (TPI * D * E::kBytes));
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < NV; ++i) {
-                            if (i * TPI + vt < left)
-                                vr[b][i] = *(const u32x4 *)(vp + (size_t)i * (TPI * D * E::kBytes));
-                            else
-                                vr[b][i] = u32x4{0u, 0u, 0u, 0u};
-                        }
-                    }
-                }
-            }
+        u32x4 kr[NK];
+        u32x4 vr[kStepBlocks][NV];
 
-            // ---- next step's keys ----
-            if (k + 1 < k1) {
-                if (k + 1 - kt == kTableRefreshSteps) {
-                    kt = k + 1;
-                    int e = kStepBlocks * kt + lane;
-                    tbl = e < NB ? trow[e] : -1;
-                }
-                issue_k(k + 1);
-            }
-
-            // ---- online softmax (base 2; scale*log2(e) is folded into the scores) ----
+        // online-softmax update with this step's scores (base 2; scale*log2(e) is in
+        // the scores), weights handed to the value lanes through LDS
+        auto softmax_update = [&](float sc) {
             const float m_step = wave_max(sc);
             const float m_new = fmaxf(m_run, m_step);
             if (m_new > m_run) {
@@ -378,16 +343,92 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
             const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
             const float p = __builtin_amdgcn_exp2f(sc - m_ref);
             l_lane += p;
-            s_p[wave][r * kBlockTokens + (s % TPI) * NV + (s / TPI)] = p;
+            *p_wr = p;
             wave_lds_sync();
+        };
+        auto scores = [&]() -> float {
+            float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < NK; i += 2) {
+                d0 = dot16<E>(kr[i].x, kr[i].y, kr[i].z, kr[i].w, &qw[4 * i], d0);
+                d1 = dot16<E>(kr[i + 1].x, kr[i + 1].y, kr[i + 1].z, kr[i + 1].w, &qw[4 * i + 4], d1);
+            }
+            return (d0 + d1) * sh.scale_log2e;
+        };
 
-            // ---- out += p * V ----
+        // ---- steps with 64 valid tokens: no masks, keys of the next step in flight ----
+        // (the last of them is peeled so that the prefetch inside the loop is unconditional)
+        int bid = 0;
+        auto load_keys = [&](int k) {
+            bid = flag_bad(row_block(k));
+            const char *kp = k_head + (size_t)bid * block_bytes;
+#pragma unroll
+            for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
+        };
+        auto full_step = [&](int k, auto prefetch) {
+            const float sc = scores();
 #pragma unroll
             for (int b = 0; b < kStepBlocks; ++b) {
-                if (vok[b]) {
+                const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
+                const char *vp = v_head + (size_t)bb * block_bytes;
+#pragma unroll
+                for (int i = 0; i < NV; ++i) vr[b][i] = *(const u32x4 *)(vp + i * (TPI * kRowBytes));
+            }
+            if constexpr (decltype(prefetch)::value) load_keys(k + 1);
+            softmax_update(sc);
+#pragma unroll
+            for (int b = 0; b < kStepBlocks; ++b) {
+                float pv[NV];
+#pragma unroll
+                for (int i = 0; i < NV; ++i) pv[i] = p_rd[b * kBlockTokens + i];
+#pragma unroll
+                for (int i = 0; i < NV; ++i)
+                    axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
+            }
+            wave_lds_sync();
+        };
+        if (k0 < kf) {
+            load_keys(k0);
+            for (int k = k0; k < kf - 1; ++k) full_step(k, std::true_type{});
+            full_step(kf - 1, std::false_type{});
+        }
+
+        // ---- the job's last, partly filled step: rows and tokens past L are masked ----
+        if (kf < k1) {
+            const int k = kf;
+            const int raw = row_block(k);
+            const bool row_ok = (kStepBlocks * k + r) < NB;
+            bid = row_ok ? flag_bad(raw) : 0;
+#pragma unroll
+            for (int i = 0; i < NK; ++i) kr[i] = u32x4{0u, 0u, 0u, 0u};
+            if (row_ok) {
+                const char *kp = k_head + (size_t)bid * block_bytes;
+#pragma unroll
+                for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
+            }
+            const int nbk = NB - kStepBlocks * k;  // 1..4 blocks in this step
+#pragma unroll
+            for (int b = 0; b < kStepBlocks; ++b) {
+#pragma unroll
+                for (int i = 0; i < NV; ++i) vr[b][i] = u32x4{0u, 0u, 0u, 0u};
+                if (b < nbk) {
+                    const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
+                    const char *vp = v_head + (size_t)bb * block_bytes;
+                    const int left = L - (kStepBlocks * k + b) * kBlockTokens;  // valid slots of this block
+#pragma unroll
+                    for (int i = 0; i < NV; ++i)
+                        if (i * TPI + vt < left) vr[b][i] = *(const u32x4 *)(vp + i * (TPI * kRowBytes));
+                }
+            }
+            const int t = (kStepBlocks * k + r) * kBlockTokens + s;
+            const float sc = (t < L) ? scores() : -INFINITY;
+            softmax_update(sc);
+#pragma unroll
+            for (int b = 0; b < kStepBlocks; ++b) {
+                if (b < nbk) {
                     float pv[NV];
 #pragma unroll
-                    for (int i = 0; i < NV; ++i) pv[i] = s_p[wave][b * kBlockTokens + vt * NV + i];
+                    for (int i = 0; i < NV; ++i) pv[i] = p_rd[b * kBlockTokens + i];
 #pragma unroll
                     for (int i = 0; i < NV; ++i)
                         axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
@@ -407,34 +448,49 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
         for (int o = 32; o > 0; o >>= 1) l_sum += __shfl_xor(l_sum, o);
 
         if (lane < LPT) {
-            if (parts_j == 1) {
+            if (k0 == 0 && k1 == steps) {
                 const float inv = l_sum > 0.f ? 1.f / l_sum : 0.f;
                 float *o = out + ((size_t)j * H + h) * D + (size_t)vc * X;
 #pragma unroll
                 for (int i = 0; i < X; ++i) o[i] = acc[i] * inv;
             } else {
-                float *o = part_acc + (size_t)it * D + (size_t)vc * X;
+                const size_t slot = (size_t)gw * 2 + (k0 > 0 ? 0 : 1);
+                float *o = part_acc + slot * D + (size_t)vc * X;
 #pragma unroll
                 for (int i = 0; i < X; ++i) o[i] = acc[i];
                 if (lane == 0) {
-                    part_ml[(size_t)it * 2] = m_run;
-                    part_ml[(size_t)it * 2 + 1] = l_sum;
+                    part_ml[slot * 2] = m_run;
+                    part_ml[slot * 2 + 1] = l_sum;
                 }
             }
+        }
+
+        // ---- next (job, head) of the range ----
+        u += k1 - k0;
+        k0 = 0;
+        if (u < hi && ++h == H) {
+            h = 0;
+            do {
+                ++j;
+            } while (j < J - 1 && s_base[j + 1] == s_base[j]);  // skip jobs without tokens
+            j = __builtin_amdgcn_readfirstlane(j);
+            L = lens[j];
+            L = L < 0 ? 0 : (L > max_len ? max_len : L);
+            steps = (L + kStepTokens - 1) / kStepTokens;
         }
     }
 }
 
 // ------------------------------------------------------------------------------------
-// Combine: one wave per (job, head) merges that pair's partitions:
+// Combine: one wave per (job, head).  A pair whose units were cut across waves
+// wa < ... < wb is merged from their partials:
 //   M = max m_i, out = sum_i 2^(m_i-M) acc_i / sum_i 2^(m_i-M) l_i.
-// Jobs with one partition were written by the partition pass; jobs with no
-// tokens get zeros here.
+// Pairs that one wave finished are left alone; jobs without tokens get zeros.
 // ------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
     const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H)
+    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H, int32_t num_waves)
 {
     constexpr int PER = D / 64;
     const int lane = threadIdx.x & 63;
@@ -443,28 +499,41 @@ __global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
     if (jh >= J * H) return;
     const int j = jh / H, h = jh - j * H;
     const int base = plan[j];
-    const int n = plan[j + 1] - base;
+    const int steps = plan[j + 1] - base;
     float *o = out + (size_t)jh * D + lane * PER;
-    if (n == 1) return;
-    if (n == 0) {
+    if (steps == 0) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) o[i] = 0.f;
         return;
     }
+    const long long S = (long long)plan[J] * H, nw = num_waves;
+    const long long u0 = (long long)base * H + (long long)h * steps;
+    const long long wa = wave_of_unit(u0, S, nw), wb = wave_of_unit(u0 + steps - 1, S, nw);
+    if (wa == wb) return;
+    // Walk the waves whose ranges overlap the pair (when there are more waves than
+    // units some ranges are empty and are stepped over).  The first wave of the pair
+    // left slot 1, every later one slot 0.  Online merge, in wave order.
     float M = -INFINITY;
-    for (int p = 0; p < n; ++p) M = fmaxf(M, part_ml[((size_t)(base + p) * H + h) * 2]);
-    const float m_ref = (M == -INFINITY) ? 0.f : M;
     float acc[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) acc[i] = 0.f;
     float l = 0.f;
-    for (int p = 0; p < n; ++p) {
-        const size_t it = (size_t)(base + p) * H + h;
-        const float w = __builtin_amdgcn_exp2f(part_ml[it * 2] - m_ref);
-        l = fmaf(w, part_ml[it * 2 + 1], l);
-        const float *a = part_acc + it * D + lane * PER;
+    const long long u1 = u0 + steps;
+    long long w = wa;
+    for (long long u = u0; u < u1;) {
+        const size_t slot = (size_t)w * 2 + (w == wa ? 1 : 0);
+        const float m_p = part_ml[slot * 2];
+        const float M_new = fmaxf(M, m_p);
+        const float m_ref = (M_new == -INFINITY) ? 0.f : M_new;
+        const float keep = __builtin_amdgcn_exp2f(M - m_ref);
+        const float wgt = __builtin_amdgcn_exp2f(m_p - m_ref);
+        l = fmaf(wgt, part_ml[slot * 2 + 1], l * keep);
+        const float *a = part_acc + slot * D + lane * PER;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] = fmaf(w, a[i], acc[i]);
+        for (int i = 0; i < PER; ++i) acc[i] = fmaf(wgt, a[i], acc[i] * keep);
+        M = M_new;
+        u = range_lo(w + 1, S, nw);  // first unit past this wave's range
+        if (u < u1) w = wave_of_unit(u, S, nw);
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
@@ -556,6 +625,43 @@ __global__ __launch_bounds__(kThreads) void fs_kv_prefill_kernel(
     *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
 }
 
+// ------------------------------------------------------------------------------------
+// Plain streaming kernels of known size: the practical HBM ceiling on this GPU and the
+// scale factor of the hardware byte counters.  Not part of the decode path.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void fs_stream_read_kernel(const u32x4 *__restrict__ src, size_t nvec,
+                                                                  u32x4 *__restrict__ sink)
+{
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    u32x4 a = u32x4{0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < nvec; i += 8 * stride) {
+        u32x4 t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a ^= t[u];
+    }
+    for (; i < nvec; i += stride) a ^= src[i];
+    // the store keeps the loads alive; it fires for one thread at most
+    if ((a.x ^ a.y ^ a.z ^ a.w) == 0x9E3779B9u && blockIdx.x == 0 && threadIdx.x == 0) sink[0] = a;
+}
+
+__global__ __launch_bounds__(kThreads) void fs_stream_copy_kernel(u32x4 *__restrict__ dst,
+                                                                  const u32x4 *__restrict__ src, size_t nvec)
+{
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        u32x4 t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dst[i + u * stride] = t[u];
+    }
+    for (; i < nvec; i += stride) dst[i] = src[i];
+}
+
 struct ProfileRecord {
     int kind;
     hipEvent_t start, stop;
@@ -574,9 +680,9 @@ struct fs_pool {
     int elem_bytes = 2;
     float scale = 0.f;
     int max_jobs = 1024;
-    int target_items = 0;
-    int wgs_per_cu = 3;
-    int items_cap = 0;
+    int wgs_per_cu = 2;      // persistent workgroups per CU of the attention grid
+    int max_workgroups = 0;  // optional cap on that grid (0 = none)
+    int waves_cap = 0;       // waves the partial buffers are sized for
     float *part_acc = nullptr;
     float *part_ml = nullptr;
     int32_t *plan = nullptr;
@@ -595,22 +701,15 @@ bool on_pool_device(const fs_pool *p) {
     return hipGetDevice(&dev) == hipSuccess && dev == p->device;
 }
 
+constexpr int kMaxWgsPerCu = 8;
+
 int alloc_scratch(fs_pool *p) {
-    const int H = p->cfg.num_heads, D = p->cfg.head_dim;
-    const int jobs = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
-    const long long cap = (long long)p->target_items + (long long)jobs * H;
-    if (cap > (1LL << 30)) return FS_ERR_INVALID_ARG;
-    float *acc = nullptr, *ml = nullptr;
-    if (hipMalloc((void **)&acc, (size_t)cap * D * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
-    if (hipMalloc((void **)&ml, (size_t)cap * 2 * sizeof(float)) != hipSuccess) {
-        (void)hipFree(acc);
-        return FS_ERR_OOM;
-    }
-    if (p->part_acc) (void)hipFree(p->part_acc);
-    if (p->part_ml) (void)hipFree(p->part_ml);
-    p->part_acc = acc;
-    p->part_ml = ml;
-    p->items_cap = (int)cap;
+    // two partial slots per wave of the largest grid the knobs allow
+    const int D = p->cfg.head_dim;
+    const long long waves = (long long)p->num_cus * kMaxWgsPerCu * kWavesPerWg;
+    if (hipMalloc((void **)&p->part_acc, (size_t)waves * 2 * D * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
+    if (hipMalloc((void **)&p->part_ml, (size_t)waves * 2 * 2 * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
+    p->waves_cap = (int)waves;
     return FS_OK;
 }
 
@@ -647,15 +746,15 @@ int launch_attention(fs_pool *p, const void *q, const int32_t *table, int32_t st
     sh.num_heads = p->cfg.num_heads;
     sh.table_stride = stride;
     sh.num_blocks = p->cfg.num_blocks;
-    sh.target_items = p->target_items;
-    sh.items_cap = p->items_cap;
     sh.scale_log2e = p->scale * 1.4426950408889634f;
-    const long long steps_bound = (long long)ceil_div(max_len, kStepTokens);
-    long long items_bound = (long long)J * sh.num_heads * steps_bound;
-    long long wgs = (items_bound + kWavesPerWg - 1) / kWavesPerWg;
+    // one unit = one 64-token step of one (job, head); no more waves than units can exist
+    const long long units_bound = (long long)J * sh.num_heads * ceil_div(max_len, kStepTokens);
+    long long wgs = (units_bound + kWavesPerWg - 1) / kWavesPerWg;
     const long long persistent = (long long)p->num_cus * p->wgs_per_cu;
     if (wgs > persistent) wgs = persistent;
+    if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
     if (wgs < 1) wgs = 1;
+    if (wgs * kWavesPerWg > p->waves_cap) return FS_ERR_INVALID_ARG;
     {
         ProfileScope ps(p, FS_KERNEL_ATTENTION, s);
         hipLaunchKernelGGL((fs_attn_partition_kernel<E, D>), dim3((unsigned)wgs), dim3(kThreads), 0, s,
@@ -668,7 +767,7 @@ int launch_attention(fs_pool *p, const void *q, const int32_t *table, int32_t st
         const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
         hipLaunchKernelGGL((fs_attn_combine_kernel<D>), dim3((unsigned)cw), dim3(kThreads), 0, s,
                            (const float *)p->part_acc, (const float *)p->part_ml,
-                           (const int32_t *)p->plan, out, J, sh.num_heads);
+                           (const int32_t *)p->plan, out, J, sh.num_heads, (int32_t)(wgs * kWavesPerWg));
     }
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     return FS_OK;
@@ -685,7 +784,7 @@ int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return FS_ERR_UNSUPPORTED;
     if (cfg->block_size != kBlockTokens) return FS_ERR_UNSUPPORTED;
     if (cfg->num_heads <= 0 || cfg->num_heads > 65535 || cfg->num_blocks <= 0 || cfg->num_host_blocks < 0 ||
-        cfg->max_jobs < 0 || cfg->target_items < 0 || cfg->reserved != 0 || !(cfg->scale >= 0.f) ||
+        cfg->max_jobs < 0 || cfg->max_workgroups < 0 || cfg->reserved != 0 || !(cfg->scale >= 0.f) ||
         !std::isfinite(cfg->scale))
         return FS_ERR_INVALID_ARG;
     fs_pool *p = new (std::nothrow) fs_pool();
@@ -702,8 +801,7 @@ int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
         return FS_ERR_HIP;
     }
     p->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    p->target_items = cfg->target_items > 0 ? cfg->target_items
-                                            : p->num_cus * p->wgs_per_cu * kWavesPerWg * 4;
+    p->max_workgroups = cfg->max_workgroups;
     const size_t need = p->block_bytes * (size_t)cfg->num_blocks;
     if (cfg->device_mem) {
         if (cfg->device_bytes < need || ((uintptr_t)cfg->device_mem & 255u)) {
@@ -955,18 +1053,13 @@ int fs_profile_collect(fs_pool *p, float *total_ms, int32_t *launches)
 int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
 {
     if (!p || !name) return FS_ERR_INVALID_ARG;
-    if (!std::strcmp(name, "target_items")) {
-        if (value < 1 || value > (1 << 24)) return FS_ERR_INVALID_ARG;
-        if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
-        if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
-        const int old = p->target_items;
-        p->target_items = value;
-        int rc = alloc_scratch(p);
-        if (rc != FS_OK) p->target_items = old;
-        return rc;
+    if (!std::strcmp(name, "max_workgroups")) {
+        if (value < 0) return FS_ERR_INVALID_ARG;
+        p->max_workgroups = value;
+        return FS_OK;
     }
     if (!std::strcmp(name, "wgs_per_cu")) {
-        if (value < 1 || value > 8) return FS_ERR_INVALID_ARG;
+        if (value < 1 || value > kMaxWgsPerCu) return FS_ERR_INVALID_ARG;
         p->wgs_per_cu = value;
         return FS_OK;
     }
@@ -976,26 +1069,43 @@ int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
 int fs_pool_get_param(const fs_pool *p, const char *name, int32_t *value)
 {
     if (!p || !name || !value) return FS_ERR_INVALID_ARG;
-    if (!std::strcmp(name, "target_items")) *value = p->target_items;
+    if (!std::strcmp(name, "max_workgroups")) *value = p->max_workgroups;
     else if (!std::strcmp(name, "wgs_per_cu")) *value = p->wgs_per_cu;
     else if (!std::strcmp(name, "num_cus")) *value = p->num_cus;
-    else if (!std::strcmp(name, "items_cap")) *value = p->items_cap;
     else if (!std::strcmp(name, "max_jobs_per_launch")) *value = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
     else return FS_ERR_INVALID_ARG;
     return FS_OK;
 }
 
-int fs_pool_last_plan(fs_pool *p, int32_t J, int32_t *item_base, int32_t *steps_per_partition, void *stream)
+int fs_pool_last_plan(fs_pool *p, int32_t J, int32_t *step_base, void *stream)
 {
-    if (!p || !item_base || !steps_per_partition || J < 0 || J > kMaxJobsPerLaunch) return FS_ERR_INVALID_ARG;
+    if (!p || !step_base || J < 0 || J > kMaxJobsPerLaunch) return FS_ERR_INVALID_ARG;
     if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     if (hipStreamSynchronize(s) != hipSuccess) return FS_ERR_HIP;
-    if (hipMemcpy(item_base, p->plan, (size_t)(J + 1) * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
-        return FS_ERR_HIP;
-    if (hipMemcpy(steps_per_partition, p->plan + J + 1, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    if (hipMemcpy(step_base, p->plan, (size_t)(J + 1) * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
         return FS_ERR_HIP;
     return FS_OK;
+}
+
+int fs_stream_read(const void *src, size_t bytes, void *sink, int32_t workgroups, void *stream)
+{
+    if (!src || !sink || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)sink & 15) ||
+        workgroups < 1 || workgroups > (1 << 20))
+        return FS_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(fs_stream_read_kernel, dim3((unsigned)workgroups), dim3(kThreads), 0, (hipStream_t)stream,
+                       (const u32x4 *)src, bytes / 16, (u32x4 *)sink);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups, void *stream)
+{
+    if (!src || !dst || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||
+        workgroups < 1 || workgroups > (1 << 20))
+        return FS_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(fs_stream_copy_kernel, dim3((unsigned)workgroups), dim3(kThreads), 0, (hipStream_t)stream,
+                       (u32x4 *)dst, (const u32x4 *)src, bytes / 16);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
 const char *fs_strerror(int status)

@@ -54,7 +54,7 @@ def test_long_context_reduced_job_count(rep):
     cfg = wl.CONFIGS[4].scaled(num_jobs=2, max_len=8192, num_heads=16)
     print(f"[case] long context reduced rep {rep}", flush=True)
     case = hs.make_case(cfg, rep)
-    got, img = run_full_step(case, fill="prefill", target_items=512)
+    got, img = run_full_step(case, fill="prefill")
     want_img = hs.expected_image(case, case.step.tables.table, case.step.tables.num_blocks)
     assert np.array_equal(img.view(np.uint8), want_img.view(np.uint8))
     hs.assert_parity(got, hs.oracle_step(case), f"long_context reduced rep {rep}")
@@ -113,33 +113,27 @@ def test_block_and_step_boundaries(dtype, D):
     assert np.array_equal(got[0].astype(np.float64), v0)
 
 
-@pytest.mark.parametrize("target", [1, 7, 64, 100000])
-def test_partition_sizes_do_not_change_the_result(target):
-    # target_items steers how many 64-token steps one partition holds: from one
-    # partition per job (no combine) to one step per partition (long combine)
+@pytest.mark.parametrize("wgs", [1, 2, 7, 33, 0])
+def test_grid_size_does_not_change_the_result(wgs):
+    # the batch's 64-token steps are dealt evenly to the waves of the grid: with one
+    # workgroup four waves walk many (job, head) pairs each; with the full grid most
+    # pairs are cut across several waves and merged by the combine pass
     cfg = wl.CONFIGS[3].scaled(num_jobs=9, num_heads=4)
     case = hs.make_case(cfg, 2, lens=[64, 65, 640, 641, 2048, 2047, 1, 1537, 300])
-    got, _ = run_full_step(case, target_items=target)
-    hs.assert_parity(got, hs.oracle_step(case), f"target_items={target}")
+    got, _ = run_full_step(case, max_workgroups=wgs)
+    hs.assert_parity(got, hs.oracle_step(case), f"max_workgroups={wgs}")
 
 
-def test_partition_plan_covers_every_step_once():
+def test_step_plan_is_the_prefix_sum_of_64_token_steps():
     cfg = wl.CONFIGS[3].scaled(num_jobs=9, num_heads=4)
     lens = np.array([64, 65, 640, 641, 2048, 2047, 1, 1537, 300], dtype=np.int32)
     case = hs.make_case(cfg, 2, lens=lens)
-    run = hs.DeviceRun(case, target_items=64)
+    run = hs.DeviceRun(case)
     try:
         run.append()
         run.attention()
-        base, P = run.pool.last_plan(cfg.num_jobs)
-        steps = (lens + 63) // 64
-        total = int(steps.sum())
-        assert P == max(1, -(-total * cfg.num_heads // 64))
-        parts = np.diff(base)
-        for n, s in zip(parts, steps):
-            chunk = -(-s // (-(-s // P)))
-            assert n == -(-s // chunk) and (n - 1) * chunk < s <= n * chunk
-        assert base[0] == 0 and base[-1] * cfg.num_heads <= run.pool.get_param("items_cap")
+        base = run.pool.last_plan(cfg.num_jobs)
+        assert np.array_equal(base, np.concatenate([[0], np.cumsum((lens + 63) // 64)]))
     finally:
         run.close()
 
@@ -199,7 +193,7 @@ def test_more_jobs_than_one_launch_slice():
     # max_jobs=8 forces three slices of the batch through the same scratch
     cfg = wl.CONFIGS[2].scaled(num_jobs=20, num_heads=3)
     case = hs.make_case(cfg, 0)
-    got, _ = run_full_step(case, max_jobs=8, target_items=16)
+    got, _ = run_full_step(case, max_jobs=8, max_workgroups=3)
     hs.assert_parity(got, hs.oracle_step(case), "sliced batch")
 
 
