@@ -217,6 +217,8 @@ def main():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the plain stream read/copy kernels over 1 GiB (scale of hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by head with no exchange; "
@@ -235,6 +237,17 @@ def main():
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
     pool_kw = {}
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            fs.fs_stream_read(src, sink, 2048)
+            fs.fs_stream_copy(dst, src, 2048)
+        torch.cuda.synchronize()
+        log("calibration: 3x fs_stream_read_kernel and 3x fs_stream_copy_kernel over 1 GiB")
+        del src, dst
 
     def measure(idx, steps, warmup, with_cpu):
         cfg = wl.CONFIGS[idx]

@@ -65,11 +65,10 @@ __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(
 // dot of one 16-byte vector of K with the matching 16 bytes of q
 template <typename E>
 __device__ __forceinline__ float dot16(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
-                                       const uint32_t *q, float acc);
+                                       uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, float acc);
 template <>
 __device__ __forceinline__ float dot16<BF16>(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
-                                             const uint32_t *q, float acc) {
-    uint32_t q0 = q[0], q1 = q[1], q2 = q[2], q3 = q[3];
+                                             uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, float acc) {
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k0), __builtin_bit_cast(bf16x2, q0), acc, false);
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k1), __builtin_bit_cast(bf16x2, q1), acc, false);
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k2), __builtin_bit_cast(bf16x2, q2), acc, false);
@@ -78,11 +77,11 @@ __device__ __forceinline__ float dot16<BF16>(uint32_t k0, uint32_t k1, uint32_t 
 }
 template <>
 __device__ __forceinline__ float dot16<F32>(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
-                                            const uint32_t *q, float acc) {
-    acc = fmaf(as_f32(k0), as_f32(q[0]), acc);
-    acc = fmaf(as_f32(k1), as_f32(q[1]), acc);
-    acc = fmaf(as_f32(k2), as_f32(q[2]), acc);
-    acc = fmaf(as_f32(k3), as_f32(q[3]), acc);
+                                            uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, float acc) {
+    acc = fmaf(as_f32(k0), as_f32(q0), acc);
+    acc = fmaf(as_f32(k1), as_f32(q1), acc);
+    acc = fmaf(as_f32(k2), as_f32(q2), acc);
+    acc = fmaf(as_f32(k3), as_f32(q3), acc);
     return acc;
 }
 
@@ -248,7 +247,23 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     float *const p_wr = &s_p[wave][r * kBlockTokens + (s % TPI) * NV + (s / TPI)];
     const float *const p_rd = &s_p[wave][vt * NV];
 
-    // ---- the job that owns unit lo: 64-ary search of the prefix sums ----
+    auto clamp_len = [&](int len) { return len < 0 ? 0 : (len > max_len ? max_len : len); };
+    // 128 table entries of a job from step kt0 on, one per lane and window; entries
+    // past the job's blocks are read (inside the row) but never used
+    auto load_window = [&](const int32_t *row, int kt0, int &w0, int &w1) {
+        int e = kStepBlocks * kt0 + lane;
+        w0 = e < sh.table_stride ? row[e] : -1;
+        e += 64;
+        w1 = e < sh.table_stride ? row[e] : -1;
+    };
+    // first job after `from` that has tokens (J if none)
+    auto next_job = [&](int from) {
+        int n = from + 1;
+        while (n < J && s_base[n + 1] == s_base[n]) ++n;
+        return __builtin_amdgcn_readfirstlane(n);
+    };
+
+    // ---- the unit the range starts with: job by 64-ary search of the prefix sums ----
     int j;
     {
         const int key = (int)(lo / H);  // s_base[j]*H <= lo  <=>  s_base[j] <= lo / H
@@ -262,75 +277,156 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         const int c2 = __popcll(__ballot(s_base[i2] <= key));
         j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
     }
-    int L = lens[j];
-    L = L < 0 ? 0 : (L > max_len ? max_len : L);
+    int L = clamp_len(lens[j]);
     int steps = (L + kStepTokens - 1) / kStepTokens;
-    int h, k0;
+    int NB = (L + kBlockTokens - 1) / kBlockTokens;
+    int h, k;
     {
         const int local = (int)(lo - (long long)__builtin_amdgcn_readfirstlane(s_base[j]) * H);
         h = local / steps;
-        k0 = local - h * steps;
+        k = local - h * steps;
+    }
+    const int32_t *trow = table + (size_t)j * sh.table_stride;
+    int kt = k & ~(kTableRefreshSteps - 1);  // table windows start at multiples of 16 steps
+    int tbl, tbl_nx;
+    load_window(trow, kt, tbl, tbl_nx);
+    // the job after this one: its length and first table window are fetched long
+    // before the walk reaches it
+    int nj = next_job(j);
+    int nL = 0, ntbl = -1, ntbl_nx = -1;
+    if (nj < J) {
+        nL = lens[nj];
+        load_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
     }
 
-    for (long long u = lo; u < hi;) {
-        const long long room = hi - u;
-        const int k1 = (long long)(steps - k0) <= room ? steps : k0 + (int)room;
-        const int kf = k1 < (L / kStepTokens) ? k1 : (L / kStepTokens);  // steps [k0, kf) hold 64 valid tokens
-        const int NB = (L + kBlockTokens - 1) / kBlockTokens;
-        const int32_t *trow = table + (size_t)j * sh.table_stride;
-
-        // q row of (j, h): wave-uniform, lives in scalar registers where it fits
-        uint32_t qw[QW];
-        {
-            const uint32_t *qrow = q + ((size_t)j * H + h) * QW;
+    // The loop below is kept free of branches around its loads: every unit issues the
+    // same loads, and what would fall outside the job (block rows past its last block,
+    // slots past its last token) is redirected to an address inside the same job whose
+    // data then gets weight zero.  Redirected loads repeat lines another lane asks for.
+    float m_run = -INFINITY;
+    float l_lane = 0.f;
+    float acc[X];
 #pragma unroll
-            for (int i = 0; i < QW; ++i) qw[i] = qrow[i];
-        }
-        const char *const k_head = pool + (size_t)h * kChunkBytes + (size_t)s * 16;
-        const char *const v_head = pool + (size_t)H * kChunkBytes + (size_t)h * kChunkBytes +
-                                   (size_t)vt * kRowBytes + (size_t)vc * 16;
+    for (int i = 0; i < X; ++i) acc[i] = 0.f;
 
-        float m_run = -INFINITY;
-        float l_lane = 0.f;
-        float acc[X];
+    // q row of the current (job, head), spread over the lanes: lane l holds 32-bit words
+    // l, l+64, ...; the scoring loop broadcasts one word at a time into a scalar register
+    constexpr int QV = (QW + 63) / 64;
+    uint32_t qv[QV];
+    auto load_q = [&](int jj, int hh) {
+        const uint32_t *qrow = q + ((size_t)jj * H + hh) * QW;
 #pragma unroll
-        for (int i = 0; i < X; ++i) acc[i] = 0.f;
+        for (int i = 0; i < QV; ++i) qv[i] = qrow[(i * 64 + lane) % QW];
+    };
+    auto q_word = [&](int w) -> uint32_t {
+        return (uint32_t)__builtin_amdgcn_readlane((int)qv[w / 64], w % 64);
+    };
+    u32x4 kr[NK];     // keys: 16-byte vector i of this lane's token
+    u32x4 vr[kStepBlocks][NV];
 
-        // table entries of 64 blocks at a time, one per lane, fetched one window ahead
-        int kt = k0;
-        int tbl, tbl_next;
-        {
-            int e = kStepBlocks * kt + lane;
-            tbl = e < NB ? trow[e] : -1;
-            e += 64;
-            tbl_next = e < NB ? trow[e] : -1;
+    // Block id of this lane's scoring row for step kk: block 4*kk+r of the job, or the
+    // job's last block for rows past it.  Walks the table window on.
+    auto row_block = [&](int kk) -> int {
+        if (kk - kt == kTableRefreshSteps) {
+            kt = kk;
+            tbl = tbl_nx;
+            int e = kStepBlocks * kt + 64 + lane;
+            tbl_nx = e < sh.table_stride ? trow[e] : -1;
         }
-        // table entry of block 4k+r (this lane's scoring row); -1 past the job's blocks
-        auto row_block = [&](int k) -> int {
-            if (k - kt == kTableRefreshSteps) {
-                kt = k;
-                tbl = tbl_next;
-                int e = kStepBlocks * kt + 64 + lane;
-                tbl_next = e < NB ? trow[e] : -1;
-            }
-            return __shfl(tbl, kStepBlocks * (k - kt) + r);
-        };
-        auto flag_bad = [&](int bid) -> int {
-            // a block id outside the pool is never dereferenced: block 0 is read in its
-            // place and the error flag is raised (the output of that job is then void)
-            if ((uint32_t)bid >= (uint32_t)sh.num_blocks) {
-                atomicOr(err, kErrBadBlock);
-                return 0;
-            }
-            return bid;
-        };
+        int bi = kStepBlocks * kk + r;
+        bi = bi < NB ? bi : NB - 1;
+        int bid = __shfl(tbl, bi - kStepBlocks * kt);
+        if ((uint32_t)bid >= (uint32_t)sh.num_blocks) {
+            // never dereferenced: block 0 is read instead and the flag raised
+            atomicOr(err, kErrBadBlock);
+            bid = 0;
+        }
+        return bid;
+    };
 
-        u32x4 kr[NK];
-        u32x4 vr[kStepBlocks][NV];
+    load_q(j, h);
+    int bid = row_block(k);
+    {
+        const char *kp = pool + (size_t)bid * block_bytes + (size_t)h * kChunkBytes + (size_t)s * 16;
+#pragma unroll
+        for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
+    }
+    int k_begin = k;  // first step of the current (job, head) that this wave handles
 
-        // online-softmax update with this step's scores (base 2; scale*log2(e) is in
-        // the scores), weights handed to the value lanes through LDS
-        auto softmax_update = [&](float sc) {
+    for (long long u = lo; u < hi; ++u) {
+        const bool last_of_pair = (k == steps - 1);
+        const bool last_of_range = (u + 1 == hi);
+        const int j_cur = j, h_cur = h;
+
+        // ---- scores of this unit's 64 tokens (base 2: scale*log2(e) folded in) ----
+        float sc;
+        {
+            float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < NK; i += 2) {
+                d0 = dot16<E>(kr[i].x, kr[i].y, kr[i].z, kr[i].w, q_word(4 * i), q_word(4 * i + 1),
+                              q_word(4 * i + 2), q_word(4 * i + 3), d0);
+                d1 = dot16<E>(kr[i + 1].x, kr[i + 1].y, kr[i + 1].z, kr[i + 1].w, q_word(4 * i + 4),
+                              q_word(4 * i + 5), q_word(4 * i + 6), q_word(4 * i + 7), d1);
+            }
+            const int t = (kStepBlocks * k + r) * kBlockTokens + s;
+            sc = t < L ? (d0 + d1) * sh.scale_log2e : -INFINITY;
+        }
+
+        // ---- values of this unit's four blocks ----
+#pragma unroll
+        for (int b = 0; b < kStepBlocks; ++b) {
+            const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
+            int bi = kStepBlocks * k + b;
+            bi = bi < NB ? bi : NB - 1;
+            const int left = L - bi * kBlockTokens;  // valid slots of that block (>= 1)
+            const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + h) * kChunkBytes + (size_t)vc * 16;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                int slot = i * TPI + vt;
+                slot = slot < left ? slot : left - 1;
+                vr[b][i] = *(const u32x4 *)(vp + (size_t)slot * kRowBytes);
+            }
+        }
+
+        // ---- the next unit: its q and keys go in flight now ----
+        if (!last_of_range) {
+            if (!last_of_pair) {
+                ++k;
+            } else {
+                k = 0;
+                if (++h == H) {  // next job: its length and first table window are already here
+                    h = 0;
+                    j = nj;
+                    L = clamp_len(nL);
+                    steps = (L + kStepTokens - 1) / kStepTokens;
+                    NB = (L + kBlockTokens - 1) / kBlockTokens;
+                    trow = table + (size_t)j * sh.table_stride;
+                    tbl = ntbl;
+                    tbl_nx = ntbl_nx;
+                    kt = 0;
+                    nj = next_job(j);
+                    if (nj < J) {
+                        nL = lens[nj];
+                        load_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
+                    }
+                } else if (kt != 0) {  // same job, next head: back to the first table window
+                    kt = 0;
+                    load_window(trow, 0, tbl, tbl_nx);
+                }
+            }
+        }
+        // (on the last unit of the range the same unit is asked for again: no branch)
+        load_q(j, h);
+        bid = row_block(k);
+        {
+            const char *kp = pool + (size_t)bid * block_bytes + (size_t)h * kChunkBytes + (size_t)s * 16;
+#pragma unroll
+            for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
+        }
+
+        // ---- online softmax; the weights reach the value lanes through LDS ----
+        {
             const float m_step = wave_max(sc);
             const float m_new = fmaxf(m_run, m_step);
             if (m_new > m_run) {
@@ -345,138 +441,51 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             l_lane += p;
             *p_wr = p;
             wave_lds_sync();
-        };
-        auto scores = [&]() -> float {
-            float d0 = 0.f, d1 = 0.f;
-#pragma unroll
-            for (int i = 0; i < NK; i += 2) {
-                d0 = dot16<E>(kr[i].x, kr[i].y, kr[i].z, kr[i].w, &qw[4 * i], d0);
-                d1 = dot16<E>(kr[i + 1].x, kr[i + 1].y, kr[i + 1].z, kr[i + 1].w, &qw[4 * i + 4], d1);
-            }
-            return (d0 + d1) * sh.scale_log2e;
-        };
-
-        // ---- steps with 64 valid tokens: no masks, keys of the next step in flight ----
-        // (the last of them is peeled so that the prefetch inside the loop is unconditional)
-        int bid = 0;
-        auto load_keys = [&](int k) {
-            bid = flag_bad(row_block(k));
-            const char *kp = k_head + (size_t)bid * block_bytes;
-#pragma unroll
-            for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
-        };
-        auto full_step = [&](int k, auto prefetch) {
-            const float sc = scores();
-#pragma unroll
-            for (int b = 0; b < kStepBlocks; ++b) {
-                const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
-                const char *vp = v_head + (size_t)bb * block_bytes;
-#pragma unroll
-                for (int i = 0; i < NV; ++i) vr[b][i] = *(const u32x4 *)(vp + i * (TPI * kRowBytes));
-            }
-            if constexpr (decltype(prefetch)::value) load_keys(k + 1);
-            softmax_update(sc);
-#pragma unroll
-            for (int b = 0; b < kStepBlocks; ++b) {
-                float pv[NV];
-#pragma unroll
-                for (int i = 0; i < NV; ++i) pv[i] = p_rd[b * kBlockTokens + i];
-#pragma unroll
-                for (int i = 0; i < NV; ++i)
-                    axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
-            }
-            wave_lds_sync();
-        };
-        if (k0 < kf) {
-            load_keys(k0);
-            for (int k = k0; k < kf - 1; ++k) full_step(k, std::true_type{});
-            full_step(kf - 1, std::false_type{});
         }
+#pragma unroll
+        for (int b = 0; b < kStepBlocks; ++b) {
+            float pv[NV];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) pv[i] = p_rd[b * kBlockTokens + i];
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
+        }
+        wave_lds_sync();
 
-        // ---- the job's last, partly filled step: rows and tokens past L are masked ----
-        if (kf < k1) {
-            const int k = kf;
-            const int raw = row_block(k);
-            const bool row_ok = (kStepBlocks * k + r) < NB;
-            bid = row_ok ? flag_bad(raw) : 0;
+        // ---- end of this wave's share of the (job, head) pair ----
+        if (last_of_pair || last_of_range) {
+            // fold the TPI token-row classes and the per-lane sums
 #pragma unroll
-            for (int i = 0; i < NK; ++i) kr[i] = u32x4{0u, 0u, 0u, 0u};
-            if (row_ok) {
-                const char *kp = k_head + (size_t)bid * block_bytes;
+            for (int o = LPT; o < 64; o <<= 1) {
 #pragma unroll
-                for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
+                for (int i = 0; i < X; ++i) acc[i] += __shfl_xor(acc[i], o);
             }
-            const int nbk = NB - kStepBlocks * k;  // 1..4 blocks in this step
+            float l_sum = l_lane;
 #pragma unroll
-            for (int b = 0; b < kStepBlocks; ++b) {
+            for (int o = 32; o > 0; o >>= 1) l_sum += __shfl_xor(l_sum, o);
+            if (lane < LPT) {
+                if (k_begin == 0 && last_of_pair) {
+                    const float inv = l_sum > 0.f ? 1.f / l_sum : 0.f;
+                    float *o = out + ((size_t)j_cur * H + h_cur) * D + (size_t)vc * X;
 #pragma unroll
-                for (int i = 0; i < NV; ++i) vr[b][i] = u32x4{0u, 0u, 0u, 0u};
-                if (b < nbk) {
-                    const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
-                    const char *vp = v_head + (size_t)bb * block_bytes;
-                    const int left = L - (kStepBlocks * k + b) * kBlockTokens;  // valid slots of this block
+                    for (int i = 0; i < X; ++i) o[i] = acc[i] * inv;
+                } else {
+                    const size_t slot = (size_t)gw * 2 + (k_begin > 0 ? 0 : 1);
+                    float *o = part_acc + slot * D + (size_t)vc * X;
 #pragma unroll
-                    for (int i = 0; i < NV; ++i)
-                        if (i * TPI + vt < left) vr[b][i] = *(const u32x4 *)(vp + i * (TPI * kRowBytes));
+                    for (int i = 0; i < X; ++i) o[i] = acc[i];
+                    if (lane == 0) {
+                        part_ml[slot * 2] = m_run;
+                        part_ml[slot * 2 + 1] = l_sum;
+                    }
                 }
             }
-            const int t = (kStepBlocks * k + r) * kBlockTokens + s;
-            const float sc = (t < L) ? scores() : -INFINITY;
-            softmax_update(sc);
+            m_run = -INFINITY;
+            l_lane = 0.f;
 #pragma unroll
-            for (int b = 0; b < kStepBlocks; ++b) {
-                if (b < nbk) {
-                    float pv[NV];
-#pragma unroll
-                    for (int i = 0; i < NV; ++i) pv[i] = p_rd[b * kBlockTokens + i];
-#pragma unroll
-                    for (int i = 0; i < NV; ++i)
-                        axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
-                }
-            }
-            wave_lds_sync();
-        }
-
-        // ---- fold the TPI token-row classes and the per-lane sums ----
-#pragma unroll
-        for (int o = LPT; o < 64; o <<= 1) {
-#pragma unroll
-            for (int i = 0; i < X; ++i) acc[i] += __shfl_xor(acc[i], o);
-        }
-        float l_sum = l_lane;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) l_sum += __shfl_xor(l_sum, o);
-
-        if (lane < LPT) {
-            if (k0 == 0 && k1 == steps) {
-                const float inv = l_sum > 0.f ? 1.f / l_sum : 0.f;
-                float *o = out + ((size_t)j * H + h) * D + (size_t)vc * X;
-#pragma unroll
-                for (int i = 0; i < X; ++i) o[i] = acc[i] * inv;
-            } else {
-                const size_t slot = (size_t)gw * 2 + (k0 > 0 ? 0 : 1);
-                float *o = part_acc + slot * D + (size_t)vc * X;
-#pragma unroll
-                for (int i = 0; i < X; ++i) o[i] = acc[i];
-                if (lane == 0) {
-                    part_ml[slot * 2] = m_run;
-                    part_ml[slot * 2 + 1] = l_sum;
-                }
-            }
-        }
-
-        // ---- next (job, head) of the range ----
-        u += k1 - k0;
-        k0 = 0;
-        if (u < hi && ++h == H) {
-            h = 0;
-            do {
-                ++j;
-            } while (j < J - 1 && s_base[j + 1] == s_base[j]);  // skip jobs without tokens
-            j = __builtin_amdgcn_readfirstlane(j);
-            L = lens[j];
-            L = L < 0 ? 0 : (L > max_len ? max_len : L);
-            steps = (L + kStepTokens - 1) / kStepTokens;
+            for (int i = 0; i < X; ++i) acc[i] = 0.f;
+            k_begin = 0;
         }
     }
 }
