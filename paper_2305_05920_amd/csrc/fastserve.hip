@@ -42,12 +42,23 @@
 #define FS_ATTN_OCCUPANCY_ATTR
 #endif
 
+// Experiments may record per-wave timestamps of the attention kernel: -DFS_TRACE
+#ifdef FS_TRACE
+#define FS_TRACE_STAMP(slot)                                                              \
+    do {                                                                                   \
+        if (lane == 0) trace_buf[((size_t)blockIdx.x * kWavesPerWg + wave) * 8 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define FS_TRACE_STAMP(slot) do { } while (0)
+#endif
+
 namespace {
 
 constexpr int kBlockTokens = 16;       // tokens per pool block
 constexpr int kStepTokens = 64;        // tokens one wave scores per step
 constexpr int kStepBlocks = kStepTokens / kBlockTokens;
 constexpr int kWavesPerWg = 4;
+constexpr int kXcds = 8;                // accelerator dies; workgroup b is dispatched to die b % 8
 constexpr int kThreads = 64 * kWavesPerWg;
 constexpr int kJobsPerThread = 4;
 constexpr int kMaxJobsPerLaunch = kThreads * kJobsPerThread;  // 1024
@@ -167,7 +178,11 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     const uint32_t *__restrict__ q, const char *__restrict__ pool,
     const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
     float *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    int32_t *__restrict__ plan, int32_t *__restrict__ err, AttnShape sh)
+    int32_t *__restrict__ plan, int32_t *__restrict__ err, AttnShape sh
+#ifdef FS_TRACE
+    , unsigned long long *__restrict__ trace_buf
+#endif
+    )
 {
     constexpr int X = 16 / E::kBytes;        // elements per 16-byte vector
     constexpr int NK = D / X;                // 16-byte vectors per token row
@@ -179,7 +194,8 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     constexpr int kChunkBytes = kBlockTokens * kRowBytes;  // one (block, head) K or V chunk
     static_assert(NK >= 2 && NK <= 32 && TPI * LPT == 64 && NV * TPI == kBlockTokens, "shape");
 
-    __shared__ int s_base[kMaxJobsPerLaunch + 1];
+    __shared__ int s_base[kMaxJobsPerLaunch + 1];  // prefix sum of steps per job
+    __shared__ int s_len[kMaxJobsPerLaunch];       // job lengths, clamped to the table
     __shared__ int s_red[kWavesPerWg];
     __shared__ float s_p[kWavesPerWg][kStepTokens];
 
@@ -189,6 +205,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     const int J = sh.num_jobs, H = sh.num_heads;
     const int max_len = sh.table_stride * kBlockTokens;
     const size_t block_bytes = (size_t)2 * H * kChunkBytes;
+    FS_TRACE_STAMP(0);
 
     // ---- prefix sum of steps per job, in LDS ----
     int st[kJobsPerThread];
@@ -206,6 +223,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             int L = Lr[i];
             bad |= (L < 0) | (L > max_len);
             L = L < 0 ? 0 : (L > max_len ? max_len : L);
+            if (tid * kJobsPerThread + i < J) s_len[tid * kJobsPerThread + i] = L;
             st[i] = (L + kStepTokens - 1) / kStepTokens;
             tot += st[i];
         }
@@ -235,10 +253,23 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     // ---- this wave's range of units ----
     const long long S = (long long)__builtin_amdgcn_readfirstlane(s_base[J]) * H;
     const long long nw = (long long)gridDim.x * kWavesPerWg;
-    const long long gw = (long long)blockIdx.x * kWavesPerWg + wave;
+    // Workgroup b runs on XCD b % 8 (round-robin dispatch).  Ranges are handed out
+    // XCD-major, so that each XCD walks one contiguous eighth of the batch -- whole
+    // jobs, hence every head and with it every memory channel in equal measure --
+    // and keeps a job's table rows and queries in its own L2.
+    long long gw;
+    {
+        const int G = gridDim.x, b = blockIdx.x;
+        const int x = b % kXcds, idx = b / kXcds;
+        // workgroups on XCDs before x: sum over y < x of ceil((G - y) / 8)
+        const int full = G / kXcds, extra = G % kXcds;
+        const int before = x * full + (x < extra ? x : extra);
+        gw = (long long)(before + idx) * kWavesPerWg + wave;
+    }
     const long long lo = range_lo(gw, S, nw);
     const long long hi = range_lo(gw + 1, S, nw);
     if (lo >= hi) return;
+    FS_TRACE_STAMP(1);
 
     const int r = lane >> 4;   // scoring: which of the step's 4 blocks
     const int s = lane & 15;   //          which slot of that block
@@ -247,7 +278,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     float *const p_wr = &s_p[wave][r * kBlockTokens + (s % TPI) * NV + (s / TPI)];
     const float *const p_rd = &s_p[wave][vt * NV];
 
-    auto clamp_len = [&](int len) { return len < 0 ? 0 : (len > max_len ? max_len : len); };
     // 128 table entries of a job from step kt0 on, one per lane and window; entries
     // past the job's blocks are read (inside the row) but never used
     auto load_window = [&](const int32_t *row, int kt0, int &w0, int &w1) {
@@ -277,7 +307,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         const int c2 = __popcll(__ballot(s_base[i2] <= key));
         j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
     }
-    int L = clamp_len(lens[j]);
+    int L = __builtin_amdgcn_readfirstlane(s_len[j]);
     int steps = (L + kStepTokens - 1) / kStepTokens;
     int NB = (L + kBlockTokens - 1) / kBlockTokens;
     int h, k;
@@ -295,7 +325,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     int nj = next_job(j);
     int nL = 0, ntbl = -1, ntbl_nx = -1;
     if (nj < J) {
-        nL = lens[nj];
+        nL = __builtin_amdgcn_readfirstlane(s_len[nj]);
         load_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
     }
 
@@ -352,6 +382,10 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
     }
     int k_begin = k;  // first step of the current (job, head) that this wave handles
+    FS_TRACE_STAMP(2);
+#ifdef FS_TRACE
+    bool first_unit = true;
+#endif
 
     for (long long u = lo; u < hi; ++u) {
         const bool last_of_pair = (k == steps - 1);
@@ -372,6 +406,14 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             const int t = (kStepBlocks * k + r) * kBlockTokens + s;
             sc = t < L ? (d0 + d1) * sh.scale_log2e : -INFINITY;
         }
+#ifdef FS_TRACE
+        if (first_unit) {
+            if (sc == 12345.678f) trace_buf[0] = 0;  // keeps the stamp behind the scores
+            FS_TRACE_STAMP(3);
+            first_unit = false;
+        }
+        if (last_of_range) FS_TRACE_STAMP(4);
+#endif
 
         // ---- values of this unit's four blocks ----
 #pragma unroll
@@ -398,7 +440,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 if (++h == H) {  // next job: its length and first table window are already here
                     h = 0;
                     j = nj;
-                    L = clamp_len(nL);
+                    L = nL;
                     steps = (L + kStepTokens - 1) / kStepTokens;
                     NB = (L + kBlockTokens - 1) / kBlockTokens;
                     trow = table + (size_t)j * sh.table_stride;
@@ -407,7 +449,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                     kt = 0;
                     nj = next_job(j);
                     if (nj < J) {
-                        nL = lens[nj];
+                        nL = __builtin_amdgcn_readfirstlane(s_len[nj]);
                         load_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
                     }
                 } else if (kt != 0) {  // same job, next head: back to the first table window
@@ -488,6 +530,13 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             k_begin = 0;
         }
     }
+    FS_TRACE_STAMP(5);
+#ifdef FS_TRACE
+    if (lane == 0) {
+        trace_buf[((size_t)blockIdx.x * kWavesPerWg + wave) * 8 + 6] = __builtin_amdgcn_s_getreg(63492);  // HW_ID
+        trace_buf[((size_t)blockIdx.x * kWavesPerWg + wave) * 8 + 7] = __builtin_amdgcn_s_getreg(63508);  // XCC_ID
+    }
+#endif
 }
 
 // ------------------------------------------------------------------------------------
@@ -696,6 +745,9 @@ struct fs_pool {
     float *part_ml = nullptr;
     int32_t *plan = nullptr;
     int32_t *err = nullptr;
+#ifdef FS_TRACE
+    unsigned long long *trace = nullptr;
+#endif
     bool profiling = false;
     std::vector<ProfileRecord> records;
     std::vector<ProfileRecord> spare;
@@ -719,6 +771,10 @@ int alloc_scratch(fs_pool *p) {
     if (hipMalloc((void **)&p->part_acc, (size_t)waves * 2 * D * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
     if (hipMalloc((void **)&p->part_ml, (size_t)waves * 2 * 2 * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
     p->waves_cap = (int)waves;
+#ifdef FS_TRACE
+    if (hipMalloc((void **)&p->trace, (size_t)waves * 8 * sizeof(unsigned long long)) != hipSuccess) return FS_ERR_OOM;
+    (void)hipMemset(p->trace, 0, (size_t)waves * 8 * sizeof(unsigned long long));
+#endif
     return FS_OK;
 }
 
@@ -768,7 +824,11 @@ int launch_attention(fs_pool *p, const void *q, const int32_t *table, int32_t st
         ProfileScope ps(p, FS_KERNEL_ATTENTION, s);
         hipLaunchKernelGGL((fs_attn_partition_kernel<E, D>), dim3((unsigned)wgs), dim3(kThreads), 0, s,
                            (const uint32_t *)q, (const char *)p->mem, table, lens, out, p->part_acc,
-                           p->part_ml, p->plan, p->err, sh);
+                           p->part_ml, p->plan, p->err, sh
+#ifdef FS_TRACE
+                           , p->trace
+#endif
+                           );
     }
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     {
@@ -1116,6 +1176,15 @@ int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups,
                        (u32x4 *)dst, (const u32x4 *)src, bytes / 16);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
+
+#ifdef FS_TRACE
+int fs_debug_trace(fs_pool *p, void *host, size_t bytes)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
+    size_t cap = (size_t)p->waves_cap * 8 * sizeof(unsigned long long);
+    return hipMemcpy(host, p->trace, bytes < cap ? bytes : cap, hipMemcpyDeviceToHost) == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+#endif
 
 const char *fs_strerror(int status)
 {
