@@ -458,11 +458,13 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 }
             }
         }
-        // (on the last unit of the range the same unit is asked for again: no branch)
+        // (the range's last unit has no successor: its loads are pointed at the first
+        // 4 KiB of the pool, one hot set of lines for every wave, instead of a branch)
         load_q(j, h);
         bid = row_block(k);
         {
             const char *kp = pool + (size_t)bid * block_bytes + (size_t)h * kChunkBytes + (size_t)s * 16;
+            kp = last_of_range ? pool + (size_t)s * 16 : kp;
 #pragma unroll
             for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
         }
