@@ -148,6 +148,21 @@ int fs_decode_attention(const void *q, fs_pool *pool, const int32_t *block_table
                         int32_t table_stride, const int32_t *job_lens, int32_t num_jobs,
                         int32_t max_len_hint, float *out, void *stream);
 
+/* ---- fused decode step (Sections 2.2 and 5: one iteration appends and attends; the
+ *      paper's engine fuses operations into fewer kernels) ---------------------------
+ * Same result as fs_kv_append(pool, table, stride, job_lens, J, k, v) followed by
+ * fs_decode_attention over job_lens[j] + 1 tokens, in one kernel launch fewer: the
+ * attention kernel takes the new token's key and value from k, v and writes them
+ * into the pool itself.
+ *   job_lens: device int32 [num_jobs], tokens cached BEFORE this step (as for append)
+ *   k, v, q:  device [num_jobs][H][D], pool dtype;  out: device float32 [num_jobs][H][D]
+ *   max_len_hint: upper bound of max_j job_lens[j] + 1 (<= 0: table_stride*B)
+ * Sums run in a different order than in the two-call form, so outputs agree with it
+ * to rounding, not bit for bit; the pool contents afterwards are identical. */
+int fs_decode_step(fs_pool *pool, const int32_t *block_table, int32_t table_stride,
+                   const int32_t *job_lens, int32_t num_jobs, const void *k, const void *v,
+                   const void *q, int32_t max_len_hint, float *out, void *stream);
+
 /* ---- block offload / upload (Section 4.2: key-value tensors of inactive jobs are
  *      swapped out to host memory and swapped in before the job is scheduled) --------
  * Copies n whole blocks between pool blocks block_ids[i] and pinned host slots

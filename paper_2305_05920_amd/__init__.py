@@ -25,7 +25,7 @@ KERNEL_KINDS = ("append", "attention", "combine", "prefill")
 EXPORTS = (
     "fs_pool_create", "fs_pool_destroy", "fs_pool_block_bytes", "fs_pool_device_ptr",
     "fs_pool_write_block", "fs_pool_read_block", "fs_pool_check", "fs_kv_append", "fs_kv_prefill",
-    "fs_decode_attention", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
+    "fs_decode_attention", "fs_decode_step", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
     "fs_profile_collect", "fs_pool_set_param", "fs_pool_get_param", "fs_pool_last_plan",
     "fs_stream_read", "fs_stream_copy", "fs_strerror", "fs_version",
 )
@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_kv_append.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
     lib.fs_kv_prefill.argtypes = [vp, vp, i32, vp, vp, i32, i64, vp, vp, vp]
     lib.fs_decode_attention.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    lib.fs_decode_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, vp, vp]
     lib.fs_pool_offload.argtypes = [vp, vp, vp, i32, vp]
     lib.fs_pool_upload.argtypes = [vp, vp, vp, i32, vp]
     lib.fs_profile_enable.argtypes = [vp, i32]
@@ -282,6 +283,24 @@ def fs_decode_attention(q: torch.Tensor, pool: Pool, block_table: torch.Tensor, 
                                       _dev(job_lens, "job_lens", torch.int32), J, int(max_len_hint),
                                       _dev(out, "out", torch.float32), _stream_ptr(stream)),
         "fs_decode_attention")
+
+
+def fs_decode_step(pool: Pool, block_table: torch.Tensor, job_lens: torch.Tensor, k: torch.Tensor,
+                   v: torch.Tensor, q: torch.Tensor, out: torch.Tensor, max_len_hint: int = 0,
+                   stream=None) -> None:
+    """Append k, v at position job_lens[j] and attend over job_lens[j] + 1 tokens, one launch fewer."""
+    J = job_lens.numel()
+    shape = (J, pool.num_heads, pool.head_dim)
+    if block_table.dim() != 2 or block_table.shape[0] != J:
+        raise ValueError("block_table: need [num_jobs][table_stride]")
+    for name, t in (("k", k), ("v", v), ("q", q), ("out", out)):
+        if tuple(t.shape) != shape:
+            raise ValueError(f"{name}: need shape {shape}")
+    _ok(pool._lib.fs_decode_step(pool._h, _dev(block_table, "block_table", torch.int32), block_table.shape[1],
+                                 _dev(job_lens, "job_lens", torch.int32), J, _dev(k, "k", pool.torch_dtype),
+                                 _dev(v, "v", pool.torch_dtype), _dev(q, "q", pool.torch_dtype),
+                                 int(max_len_hint), _dev(out, "out", torch.float32), _stream_ptr(stream)),
+        "fs_decode_step")
 
 
 def fs_pool_offload(pool: Pool, block_ids, host_slots, stream=None) -> None:

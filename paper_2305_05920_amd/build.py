@@ -16,6 +16,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # contract a*b+c only where the source writes it as one expression: a score is a
+    # rounded product, and "score - max" must be exactly 0 for the maximum itself
+    "-ffp-contract=on",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -173,10 +173,17 @@ __device__ __forceinline__ long long wave_of_unit(long long u, long long S, long
 //   that is cut by a range boundary leaves a partial (m, l, acc) per wave involved:
 //   slot 0 of the wave if the pair began before the wave's range, else slot 1.
 // ------------------------------------------------------------------------------------
-template <typename E, int D>
+//
+// kFused: the step's KV append happens here too.  `lens` then holds the lengths
+// before the append and the units cover those pool-resident tokens (one unit at
+// least per job, so that a job with an empty cache is visited too).  The new token of
+// every job comes from k_new / v_new ([J][H][D], pool dtype): the wave that owns the
+// last unit of a (job, head) scores it, adds it to the softmax state and writes its
+// key and value row into the pool (slot `lens[j]` of the job).
+template <typename E, int D, bool kFused>
 __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_partition_kernel(
-    const uint32_t *__restrict__ q, const char *__restrict__ pool,
-    const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
+    const uint32_t *__restrict__ q, const char *pool, char *pool_w, const char *__restrict__ k_new,
+    const char *__restrict__ v_new, const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
     float *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml,
     int32_t *__restrict__ plan, int32_t *__restrict__ err, AttnShape sh
 #ifdef FS_TRACE
@@ -221,10 +228,13 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 #pragma unroll
         for (int i = 0; i < kJobsPerThread; ++i) {
             int L = Lr[i];
-            bad |= (L < 0) | (L > max_len);
-            L = L < 0 ? 0 : (L > max_len ? max_len : L);
-            if (tid * kJobsPerThread + i < J) s_len[tid * kJobsPerThread + i] = L;
+            const int cap = kFused ? max_len - 1 : max_len;  // fused: room for the new token
+            bad |= (L < 0) | (L > cap);
+            L = L < 0 ? 0 : (L > cap ? cap : L);
+            const bool real = tid * kJobsPerThread + i < J;
+            if (real) s_len[tid * kJobsPerThread + i] = L;
             st[i] = (L + kStepTokens - 1) / kStepTokens;
+            if (kFused && real && st[i] == 0) st[i] = 1;
             tot += st[i];
         }
         if (bad) atomicOr(err, kErrBadLen);
@@ -307,8 +317,12 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         const int c2 = __popcll(__ballot(s_base[i2] <= key));
         j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
     }
+    auto steps_of = [](int len) {
+        const int n = (len + kStepTokens - 1) / kStepTokens;
+        return (kFused && n == 0) ? 1 : n;
+    };
     int L = __builtin_amdgcn_readfirstlane(s_len[j]);
-    int steps = (L + kStepTokens - 1) / kStepTokens;
+    int steps = steps_of(L);
     int NB = (L + kBlockTokens - 1) / kBlockTokens;
     int h, k;
     {
@@ -365,6 +379,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         }
         int bi = kStepBlocks * kk + r;
         bi = bi < NB ? bi : NB - 1;
+        if (kFused) bi = bi > 0 ? bi : 0;  // a job with an empty cache: entry 0, the block of its new token
         int bid = __shfl(tbl, bi - kStepBlocks * kt);
         if ((uint32_t)bid >= (uint32_t)sh.num_blocks) {
             // never dereferenced: block 0 is read instead and the flag raised
@@ -381,6 +396,9 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 #pragma unroll
         for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
     }
+    // fused append: q, key and value vectors of the new token of the pair being finished
+    u32x4 xq = u32x4{0u, 0u, 0u, 0u}, xk = xq, xv = xq;
+    int xbid = 0;
     int k_begin = k;  // first step of the current (job, head) that this wave handles
     FS_TRACE_STAMP(2);
 #ifdef FS_TRACE
@@ -391,6 +409,17 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         const bool last_of_pair = (k == steps - 1);
         const bool last_of_range = (u + 1 == hi);
         const int j_cur = j, h_cur = h;
+        const int L_cur = L;
+        if (kFused && last_of_pair) {
+            // the new token's vectors and the block it goes to: asked for now, used at the pair's end
+            const size_t row = ((size_t)j * H + h) * kRowBytes + (size_t)vc * 16;
+            if (lane < LPT) {
+                xq = *(const u32x4 *)((const char *)q + row);
+                xk = *(const u32x4 *)(k_new + row);
+                xv = *(const u32x4 *)(v_new + row);
+            }
+            xbid = trow[L / kBlockTokens];
+        }
 
         // ---- scores of this unit's 64 tokens (base 2: scale*log2(e) folded in) ----
         float sc;
@@ -421,12 +450,17 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
             int bi = kStepBlocks * k + b;
             bi = bi < NB ? bi : NB - 1;
-            const int left = L - bi * kBlockTokens;  // valid slots of that block (>= 1)
+            if (kFused) bi = bi > 0 ? bi : 0;
+            const int left = L - bi * kBlockTokens;  // valid slots of that block (>= 1 unless the cache is empty)
             const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + h) * kChunkBytes + (size_t)vc * 16;
+            // fused, empty cache: nothing of this job is in the pool yet; the loads read the
+            // job's own new value row instead (finite data, weight zero), slot 0 below
+            if (kFused && L == 0) vp = v_new + ((size_t)j * H + h) * kRowBytes + (size_t)vc * 16;
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 int slot = i * TPI + vt;
                 slot = slot < left ? slot : left - 1;
+                if (kFused) slot = slot > 0 ? slot : 0;
                 vr[b][i] = *(const u32x4 *)(vp + (size_t)slot * kRowBytes);
             }
         }
@@ -441,7 +475,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                     h = 0;
                     j = nj;
                     L = nL;
-                    steps = (L + kStepTokens - 1) / kStepTokens;
+                    steps = steps_of(L);
                     NB = (L + kBlockTokens - 1) / kBlockTokens;
                     trow = table + (size_t)j * sh.table_stride;
                     tbl = ntbl;
@@ -499,6 +533,40 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 
         // ---- end of this wave's share of the (job, head) pair ----
         if (last_of_pair || last_of_range) {
+            if (kFused && last_of_pair) {
+                // the appended token: score, softmax update, value; then its rows go to the pool
+                float d = dot16<E>(xk.x, xk.y, xk.z, xk.w, xq.x, xq.y, xq.z, xq.w, 0.f);  // 0 outside lanes < LPT
+#pragma unroll
+                for (int o = 1; o < LPT; o <<= 1) d += __shfl_xor(d, o);
+                // (a rounded product: the build keeps it from being contracted into the
+                // subtraction below, so a token that is its own maximum gets weight exactly 1)
+                const float s_new = as_f32((uint32_t)__builtin_amdgcn_readlane((int)as_u32(d), 0)) * sh.scale_log2e;
+                const float m_new = fmaxf(m_run, s_new);
+                const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
+                const float p_new = __builtin_amdgcn_exp2f(s_new - m_ref);
+#ifdef FS_DEBUG_EXTRA
+                if (lane == 0) {
+                    float *dbg = part_acc + (size_t)(j_cur * H + h_cur) * 8;
+                    dbg[0] = m_run; dbg[1] = s_new; dbg[2] = p_new; dbg[3] = alpha; dbg[4] = l_lane; dbg[5] = acc[0];
+                }
+#endif
+                l_lane = l_lane * alpha + (lane == 0 ? p_new : 0.f);
+#pragma unroll
+                for (int i = 0; i < X; ++i) acc[i] *= alpha;
+                axpy16<E>(lane < LPT ? p_new : 0.f, xv.x, xv.y, xv.z, xv.w, acc);
+                m_run = m_new;
+                const int pos = L_cur;  // = lens[j]: where the token goes
+                const int wb = __builtin_amdgcn_readfirstlane(xbid);
+                if ((uint32_t)wb >= (uint32_t)sh.num_blocks) {
+                    if (lane == 0) atomicOr(err, kErrBadBlock);
+                } else if (lane < LPT) {
+                    char *blk = pool_w + (size_t)wb * block_bytes;
+                    const int ps = pos % kBlockTokens;
+                    *(u32x4 *)(blk + (size_t)h_cur * kChunkBytes + ((size_t)vc * kBlockTokens + ps) * 16) = xk;
+                    *(u32x4 *)(blk + (size_t)(H + h_cur) * kChunkBytes + (size_t)ps * kRowBytes + (size_t)vc * 16) = xv;
+                }
+            }
             // fold the TPI token-row classes and the per-lane sums
 #pragma unroll
             for (int o = LPT; o < 64; o <<= 1) {
@@ -804,9 +872,9 @@ struct ProfileScope {
     }
 };
 
-template <typename E, int D>
-int launch_attention(fs_pool *p, const void *q, const int32_t *table, int32_t stride,
-                     const int32_t *lens, int32_t J, int32_t max_len, float *out, hipStream_t s)
+template <typename E, int D, bool kFused>
+int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v_new, const int32_t *table,
+                     int32_t stride, const int32_t *lens, int32_t J, int32_t max_len, float *out, hipStream_t s)
 {
     AttnShape sh;
     sh.num_jobs = J;
@@ -824,8 +892,9 @@ int launch_attention(fs_pool *p, const void *q, const int32_t *table, int32_t st
     if (wgs * kWavesPerWg > p->waves_cap) return FS_ERR_INVALID_ARG;
     {
         ProfileScope ps(p, FS_KERNEL_ATTENTION, s);
-        hipLaunchKernelGGL((fs_attn_partition_kernel<E, D>), dim3((unsigned)wgs), dim3(kThreads), 0, s,
-                           (const uint32_t *)q, (const char *)p->mem, table, lens, out, p->part_acc,
+        hipLaunchKernelGGL((fs_attn_partition_kernel<E, D, kFused>), dim3((unsigned)wgs), dim3(kThreads), 0, s,
+                           (const uint32_t *)q, (const char *)p->mem, kFused ? p->mem : (char *)nullptr,
+                           (const char *)k_new, (const char *)v_new, table, lens, out, p->part_acc,
                            p->part_ml, p->plan, p->err, sh
 #ifdef FS_TRACE
                            , p->trace
@@ -1023,12 +1092,14 @@ int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
-int fs_decode_attention(const void *q, fs_pool *p, const int32_t *table, int32_t stride,
-                        const int32_t *lens, int32_t J, int32_t max_len_hint, float *out, void *stream)
+static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_new, const void *v_new,
+                         const int32_t *table, int32_t stride, const int32_t *lens, int32_t J,
+                         int32_t max_len_hint, float *out, void *stream)
 {
     if (!p || J < 0) return FS_ERR_INVALID_ARG;
     if (J == 0) return FS_OK;
     if (!q || !table || !lens || !out || stride <= 0) return FS_ERR_INVALID_ARG;
+    if (fused && (!k_new || !v_new)) return FS_ERR_INVALID_ARG;
     if ((long long)stride * kBlockTokens > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
     if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
@@ -1040,18 +1111,35 @@ int fs_decode_attention(const void *q, fs_pool *p, const int32_t *table, int32_t
     for (int j0 = 0; j0 < J; j0 += slice) {
         const int n = (J - j0) < slice ? (J - j0) : slice;
         const void *qs = (const char *)q + (size_t)j0 * row_bytes;
+        const void *ks = fused ? (const char *)k_new + (size_t)j0 * row_bytes : nullptr;
+        const void *vs = fused ? (const char *)v_new + (size_t)j0 * row_bytes : nullptr;
         const int32_t *ts = table + (size_t)j0 * stride;
+        const int32_t *ls = lens + j0;
         float *os = out + (size_t)j0 * H * D;
         int rc;
+#define FS_LAUNCH(E, DD)                                                                                 \
+    (fused ? launch_attention<E, DD, true>(p, qs, ks, vs, ts, stride, ls, n, max_len, os, s)              \
+           : launch_attention<E, DD, false>(p, qs, ks, vs, ts, stride, ls, n, max_len, os, s))
         if (p->cfg.dtype == FS_BF16)
-            rc = D == 128 ? launch_attention<BF16, 128>(p, qs, ts, stride, lens + j0, n, max_len, os, s)
-                          : launch_attention<BF16, 64>(p, qs, ts, stride, lens + j0, n, max_len, os, s);
+            rc = D == 128 ? FS_LAUNCH(BF16, 128) : FS_LAUNCH(BF16, 64);
         else
-            rc = D == 128 ? launch_attention<F32, 128>(p, qs, ts, stride, lens + j0, n, max_len, os, s)
-                          : launch_attention<F32, 64>(p, qs, ts, stride, lens + j0, n, max_len, os, s);
+            rc = D == 128 ? FS_LAUNCH(F32, 128) : FS_LAUNCH(F32, 64);
+#undef FS_LAUNCH
         if (rc != FS_OK) return rc;
     }
     return FS_OK;
+}
+
+int fs_decode_attention(const void *q, fs_pool *p, const int32_t *table, int32_t stride,
+                        const int32_t *lens, int32_t J, int32_t max_len_hint, float *out, void *stream)
+{
+    return run_attention(p, false, q, nullptr, nullptr, table, stride, lens, J, max_len_hint, out, stream);
+}
+
+int fs_decode_step(fs_pool *p, const int32_t *table, int32_t stride, const int32_t *lens, int32_t J,
+                   const void *k, const void *v, const void *q, int32_t max_len_hint, float *out, void *stream)
+{
+    return run_attention(p, true, q, k, v, table, stride, lens, J, max_len_hint, out, stream);
 }
 
 static int copy_blocks(fs_pool *p, const int32_t *block_ids, const int32_t *host_slots, int32_t n, void *stream,
@@ -1185,6 +1273,14 @@ int fs_debug_trace(fs_pool *p, void *host, size_t bytes)
     if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
     size_t cap = (size_t)p->waves_cap * 8 * sizeof(unsigned long long);
     return hipMemcpy(host, p->trace, bytes < cap ? bytes : cap, hipMemcpyDeviceToHost) == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+#endif
+
+#ifdef FS_DEBUG_EXTRA
+int fs_debug_partials(fs_pool *p, void *host, size_t bytes)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
+    return hipMemcpy(host, p->part_acc, bytes, hipMemcpyDeviceToHost) == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 #endif
 

@@ -173,6 +173,13 @@ class DeviceRun:
         torch.cuda.synchronize()
         return self.out.cpu().numpy()
 
+    def fused_step(self, max_len_hint: int = 0) -> np.ndarray:
+        """Append + attention through the single fused entry point."""
+        self.fs.fs_decode_step(self.pool, self.table, self.lens_before, self.k_new, self.v_new, self.q,
+                               self.out, max_len_hint=max_len_hint)
+        torch.cuda.synchronize()
+        return self.out.cpu().numpy()
+
     def image(self) -> np.ndarray:
         torch.cuda.synchronize()
         return from_torch(self.case.cfg.dtype, self.mem)

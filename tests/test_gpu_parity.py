@@ -60,6 +60,134 @@ def test_long_context_reduced_job_count(rep):
     hs.assert_parity(got, hs.oracle_step(case), f"long_context reduced rep {rep}")
 
 
+def test_long_context_full_size_sampled():
+    # preset 4 at its full size (8 jobs of 16k-32k tokens, 64 heads: ~6 GB of KV) in the
+    # launch configuration bench.py times.  The oracle recomputes sampled (job, head)
+    # rows one by one; every other row must be finite and inside the convex hull bound
+    # that holds for any attention output (|out| <= max |v| over the job's cache).
+    import paper_2305_05920_amd as fs
+    cfg = wl.CONFIGS[4]
+    print("[case] preset long_context full size", flush=True)
+    case = hs.make_case(cfg, 0)
+    bt = case.step.tables
+    H, D = cfg.num_heads, cfg.head_dim
+    lay = hs.layout_of(cfg)
+    mem = torch.empty((bt.num_blocks, lay.block_elems), dtype=torch.bfloat16, device="cuda")
+    table = torch.from_numpy(bt.table).cuda()
+    with fs.Pool(cfg.dtype, H, D, bt.num_blocks, device_mem=mem) as pool:
+        for j, (K, V) in enumerate(case.caches):          # bulk write job by job
+            n = int(case.lens_before[j])
+            fs.fs_kv_prefill(pool, table[j:j + 1].contiguous(), torch.zeros(1, dtype=torch.int32, device="cuda"),
+                             torch.tensor([0, n], dtype=torch.int32, device="cuda"), n,
+                             hs.to_torch(cfg.dtype, K[:n]), hs.to_torch(cfg.dtype, V[:n]))
+            torch.cuda.synchronize()
+        fs.fs_kv_append(pool, table, torch.from_numpy(case.lens_before).cuda(),
+                        hs.to_torch(cfg.dtype, case.k_new), hs.to_torch(cfg.dtype, case.v_new))
+        out = torch.full((cfg.num_jobs, H, D), float("nan"), dtype=torch.float32, device="cuda")
+        fs.fs_decode_attention(hs.to_torch(cfg.dtype, case.step.q), pool, table,
+                               torch.from_numpy(case.step.lens).cuda(), out,
+                               max_len_hint=int(case.step.lens.max()))
+        pool.check()
+        got = out.cpu().numpy()
+        # placement: sampled blocks read back through the C ABI against the layout model
+        rng = np.random.default_rng(4)
+        for j in rng.choice(cfg.num_jobs, size=3, replace=False):
+            K, V = case.caches[j]
+            for bi in (0, int(case.step.lens[j] - 1) // 16, int(rng.integers(0, case.step.lens[j] // 16))):
+                blk = pool.read_block(int(bt.table[j, bi]), np.uint16)[None]
+                n = min(16, int(case.step.lens[j]) - bi * 16)
+                k1, v1 = lay.read_tokens(blk, np.zeros(1, dtype=np.int32), 0, n)
+                assert np.array_equal(k1, K[bi * 16:bi * 16 + n]) and np.array_equal(v1, V[bi * 16:bi * 16 + n])
+    assert np.isfinite(got).all()
+    for j, (K, V) in enumerate(case.caches):
+        vmax = wl.bf16_bits_to_f32(V).__abs__().max(axis=0)            # [H][D]
+        assert (np.abs(got[j]) <= vmax + 1e-6).all()
+    worst = 0.0
+    for _ in range(24):
+        j, h = int(rng.integers(cfg.num_jobs)), int(rng.integers(H))
+        K, V = case.caches[j]
+        ref = oracle.attention_job(case.step.q[j], K, V, cfg.dtype, heads=(h, h + 1))[h]
+        err = np.abs(got[j, h] - ref).max()
+        rel = np.linalg.norm(got[j, h] - ref) / np.linalg.norm(ref)
+        worst = max(worst, err)
+        assert err <= hs.MAX_ABS_TOL and rel <= hs.REL_L2_TOL, (j, h, err, rel)
+    print(f"[parity] long_context full size: worst sampled max_abs={worst:.3e}", flush=True)
+
+
+# ---- fused step: append inside the attention kernel -------------------------------
+@pytest.mark.parametrize("idx,rep", [(0, 0), (0, 1), (1, 0), (2, 1), (3, 2)])
+def test_fused_step_matches_oracle_and_layout(idx, rep):
+    cfg = wl.CONFIGS[idx]
+    print(f"[case] fused preset {cfg.name} rep {rep}", flush=True)
+    case = hs.make_case(cfg, rep)
+    bt = case.step.tables
+    want_img = hs.expected_image(case, bt.table, bt.num_blocks, upto="prefix")
+    run = hs.DeviceRun(case, fill="image", prefix_image=want_img)
+    try:
+        got = run.fused_step(max_len_hint=int(case.step.lens.max()))
+        run.pool.check()
+        img = run.image()
+    finally:
+        run.close()
+    hs.append_into(want_img, case, bt.table)
+    assert np.array_equal(img.view(np.uint8), want_img.view(np.uint8)), "pool image differs from the layout model"
+    hs.assert_parity(got, hs.oracle_step(case), f"fused {cfg.name} rep {rep}")
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_fused_step_boundaries(dtype, D):
+    # lengths after the append; 1 means an empty cache before the step, 65 a cache of
+    # exactly one full 64-token unit, 17 a new token that opens a new block
+    lens = [1, 2, 16, 17, 64, 65, 66, 128, 129, 1000, 1024, 1025]
+    cfg = wl.CONFIGS[1].scaled(num_jobs=len(lens), num_heads=5, head_dim=D, dtype=dtype, max_len=1040)
+    case = hs.make_case(cfg, 1, lens=lens)
+    run = hs.DeviceRun(case, fill="image")
+    try:
+        got = run.fused_step()
+        run.pool.check()
+        img = run.image()
+    finally:
+        run.close()
+    want = hs.expected_image(case, case.step.tables.table, case.step.tables.num_blocks)
+    assert np.array_equal(img.view(np.uint8), want.view(np.uint8))
+    hs.assert_parity(got, hs.oracle_step(case), f"fused edges {dtype} D={D}")
+    assert np.array_equal(got[0].astype(np.float64), wl.to_f64(dtype, case.v_new[0]))   # L = 1: its own value
+
+
+def test_fused_step_agrees_with_the_two_call_form():
+    cfg = wl.CONFIGS[3].scaled(num_jobs=16, num_heads=6)
+    case = hs.make_case(cfg, 0)
+    a = hs.DeviceRun(case)
+    b = hs.DeviceRun(case)
+    try:
+        a.append()
+        two = a.attention()
+        one = b.fused_step()
+        a.pool.check(), b.pool.check()
+        assert np.array_equal(a.image(), b.image())
+        np.testing.assert_allclose(one, two, rtol=0, atol=2e-6)
+        # an empty-cache garbage guard: stale NaN bit patterns in never-written slots must not leak
+        assert np.isfinite(one).all()
+    finally:
+        a.close(), b.close()
+
+
+def test_fused_step_flags_a_full_table_row():
+    import paper_2305_05920_amd as fs
+    cfg = wl.CONFIGS[1].scaled(num_jobs=2, num_heads=2, max_len=64)
+    case = hs.make_case(cfg, 0, lens=[40, 64], width=4)
+    run = hs.DeviceRun(case)
+    try:
+        run.fused_step()
+        run.pool.check()
+        full = torch.tensor([39, 64], dtype=torch.int32, device="cuda")     # job 1: no room for a 65th token
+        fs.fs_decode_step(run.pool, run.table, full, run.k_new, run.v_new, run.q, run.out)
+        with pytest.raises(fs.FsError):
+            run.pool.check()
+    finally:
+        run.close()
+
+
 # ---- placement alone ---------------------------------------------------------------
 @pytest.mark.parametrize("idx", [0, 1, 2])
 def test_prefill_then_append_is_bit_exact_and_touches_nothing_else(idx):
