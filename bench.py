@@ -2,8 +2,9 @@
 """Benchmark of the paged decode step on one MI355X.
 
 A step is one pass of the whole hot path over one admitted batch: KV append of
-every job's new token, then one-query-per-job attention over every job's paged
-cache (partition pass + combine).  Inputs are synthetic and seeded
+every job's new token (fs_kv_append), then one-query-per-job attention over every
+job's paged cache (fs_decode_attention: partition pass + combine).  The fused entry
+point fs_decode_step (append inside the attention kernel) is timed beside it.  Inputs are synthetic and seeded
 (fs_workload), resident in HBM before the timed region.  To keep the 256 MB
 last-level cache from serving the reads, the steps rotate over several replicas
 of the pool.
@@ -13,6 +14,7 @@ Prints ONE JSON line; see --help for the knobs.
 from __future__ import annotations
 
 import argparse
+from concurrent.futures import ThreadPoolExecutor
 import json
 import os
 import sys
@@ -63,7 +65,8 @@ class Replicas:
         self.max_len = int(step.lens.max())
         # host caches -> packed prefix tokens -> bulk write into replica 0 -> copy to the rest
         t0 = time.time()
-        self.caches = [step.cache(j) for j in range(cfg.num_jobs)]
+        with ThreadPoolExecutor(max_workers=8) as ex:      # numpy's generators release the GIL
+            self.caches = list(ex.map(step.cache, range(cfg.num_jobs)))
         log(f"generated {cfg.name}: J={cfg.num_jobs} sum(L)={step.total_tokens} "
             f"pool={pool_bytes / 1e9:.2f} GB x{R} in {time.time() - t0:.1f}s")
         offs = np.zeros(cfg.num_jobs + 1, dtype=np.int32)
@@ -99,10 +102,17 @@ class Replicas:
             return t.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(t.bfloat16)
         return t.from_numpy(np.ascontiguousarray(a)).cuda()
 
+    fused = False
+
     def run_step(self, i):
         pool = self.pools[i % self.R]
-        self.fs.fs_kv_append(pool, self.table, self.lens_before, self.k_new, self.v_new)
-        self.fs.fs_decode_attention(self.q, pool, self.table, self.lens, self.out, max_len_hint=self.max_len)
+        if self.fused:
+            self.fs.fs_decode_step(pool, self.table, self.lens_before, self.k_new, self.v_new, self.q,
+                                   self.out, max_len_hint=self.max_len)
+        else:
+            self.fs.fs_kv_append(pool, self.table, self.lens_before, self.k_new, self.v_new)
+            self.fs.fs_decode_attention(self.q, pool, self.table, self.lens, self.out,
+                                        max_len_hint=self.max_len)
 
     def close(self):
         for p in self.pools:
@@ -212,7 +222,7 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=1, help="workload preset timed as the headline (default 1)")
-    ap.add_argument("--also", type=str, default="2,3", help="other presets reported under 'other_workloads'")
+    ap.add_argument("--also", type=str, default="2,3,4", help="other presets reported under 'other_workloads'")
     ap.add_argument("--footprint-gb", type=float, default=2.0, help="bytes touched between reuses of a replica")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -256,11 +266,18 @@ def main():
             if args.wgs_per_cu:
                 for p in reps.pools:
                     p.set_param("wgs_per_cu", args.wgs_per_cu)
+            reps.fused = True
+            ms_f = time_steps(torch, reps, steps, warmup)
+            kt_f = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
+            reps.fused = False
             ms = time_steps(torch, reps, steps, warmup)
             kt = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
             res = {"workload": cfg.name, "ms_per_step": ms, "job_tokens_per_s": cfg.num_jobs / (ms / 1e3),
                    "kernel_ms": kt, "alg_bytes": reps.alg_bytes, "replicas": reps.R,
-                   "attention_gbps": reps.alg_bytes / (kt["attention"] * 1e-3) / 1e9}
+                   "attention_gbps": reps.alg_bytes / (kt["attention"] * 1e-3) / 1e9,
+                   "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
+                                  "kernel_ms": kt_f,
+                                  "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
             if not args.no_graph:
                 try:
                     res["ms_per_step_graph"] = graph_ms(torch, reps, steps)
@@ -316,6 +333,7 @@ def main():
                      "alg_bytes_per_launch": main_res["alg_bytes"]},
         "cpu_baseline": base,
         "kernel_ms": main_res["kernel_ms"],
+        "fused_step": main_res["fused_step"],
         "ms_per_step_graph": main_res.get("ms_per_step_graph"),
         "max_abs_err": main_res.get("max_abs_err"),
         "rel_l2_err": main_res.get("rel_l2_err"),

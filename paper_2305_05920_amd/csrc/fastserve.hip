@@ -62,7 +62,8 @@ constexpr int kXcds = 8;                // accelerator dies; workgroup b is disp
 constexpr int kThreads = 64 * kWavesPerWg;
 constexpr int kJobsPerThread = 4;
 constexpr int kMaxJobsPerLaunch = kThreads * kJobsPerThread;  // 1024
-constexpr int kTableRefreshSteps = 64 / kStepBlocks;          // 64 table entries per refresh
+constexpr int kWindowBlocks = 128;                            // table entries a wave keeps in LDS
+constexpr int kWindowSteps = kWindowBlocks / kStepBlocks;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -205,6 +206,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     __shared__ int s_len[kMaxJobsPerLaunch];       // job lengths, clamped to the table
     __shared__ int s_red[kWavesPerWg];
     __shared__ float s_p[kWavesPerWg][kStepTokens];
+    __shared__ int s_tbl[kWavesPerWg][kWindowBlocks];  // per wave: table entries of the current job
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -288,13 +290,19 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     float *const p_wr = &s_p[wave][r * kBlockTokens + (s % TPI) * NV + (s / TPI)];
     const float *const p_rd = &s_p[wave][vt * NV];
 
-    // 128 table entries of a job from step kt0 on, one per lane and window; entries
-    // past the job's blocks are read (inside the row) but never used
-    auto load_window = [&](const int32_t *row, int kt0, int &w0, int &w1) {
+    // The table entries [4*kt, 4*kt + 128) of the current job live in LDS (one window
+    // per wave).  Entries past the job's blocks are read (inside the row) but never used.
+    int *const w_tbl = s_tbl[wave];
+    auto fetch_window = [&](const int32_t *row, int kt0, int &w0, int &w1) {
         int e = kStepBlocks * kt0 + lane;
         w0 = e < sh.table_stride ? row[e] : -1;
         e += 64;
         w1 = e < sh.table_stride ? row[e] : -1;
+    };
+    auto store_window = [&](int w0, int w1) {
+        w_tbl[lane] = w0;
+        w_tbl[64 + lane] = w1;
+        wave_lds_sync();
     };
     // first job after `from` that has tokens (J if none)
     auto next_job = [&](int from) {
@@ -331,16 +339,19 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         k = local - h * steps;
     }
     const int32_t *trow = table + (size_t)j * sh.table_stride;
-    int kt = k & ~(kTableRefreshSteps - 1);  // table windows start at multiples of 16 steps
-    int tbl, tbl_nx;
-    load_window(trow, kt, tbl, tbl_nx);
-    // the job after this one: its length and first table window are fetched long
-    // before the walk reaches it
+    int kt = k & ~(kWindowSteps - 1);  // windows start at multiples of 32 steps
+    {
+        int w0, w1;
+        fetch_window(trow, kt, w0, w1);
+        store_window(w0, w1);
+    }
+    // the job after this one: its length and first table window are asked for long
+    // before the walk reaches it (registers that only the job change below touches)
     int nj = next_job(j);
     int nL = 0, ntbl = -1, ntbl_nx = -1;
     if (nj < J) {
         nL = __builtin_amdgcn_readfirstlane(s_len[nj]);
-        load_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
+        fetch_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
     }
 
     // The loop below is kept free of branches around its loads: every unit issues the
@@ -368,19 +379,13 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     u32x4 kr[NK];     // keys: 16-byte vector i of this lane's token
     u32x4 vr[kStepBlocks][NV];
 
-    // Block id of this lane's scoring row for step kk: block 4*kk+r of the job, or the
-    // job's last block for rows past it.  Walks the table window on.
+    // Block id of this lane's scoring row for step kk (inside the current window):
+    // block 4*kk+r of the job, or the job's last block for rows past it.
     auto row_block = [&](int kk) -> int {
-        if (kk - kt == kTableRefreshSteps) {
-            kt = kk;
-            tbl = tbl_nx;
-            int e = kStepBlocks * kt + 64 + lane;
-            tbl_nx = e < sh.table_stride ? trow[e] : -1;
-        }
         int bi = kStepBlocks * kk + r;
         bi = bi < NB ? bi : NB - 1;
         if (kFused) bi = bi > 0 ? bi : 0;  // a job with an empty cache: entry 0, the block of its new token
-        int bid = __shfl(tbl, bi - kStepBlocks * kt);
+        int bid = w_tbl[bi - kStepBlocks * kt];
         if ((uint32_t)bid >= (uint32_t)sh.num_blocks) {
             // never dereferenced: block 0 is read instead and the flag raised
             atomicOr(err, kErrBadBlock);
@@ -408,18 +413,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     for (long long u = lo; u < hi; ++u) {
         const bool last_of_pair = (k == steps - 1);
         const bool last_of_range = (u + 1 == hi);
-        const int j_cur = j, h_cur = h;
-        const int L_cur = L;
-        if (kFused && last_of_pair) {
-            // the new token's vectors and the block it goes to: asked for now, used at the pair's end
-            const size_t row = ((size_t)j * H + h) * kRowBytes + (size_t)vc * 16;
-            if (lane < LPT) {
-                xq = *(const u32x4 *)((const char *)q + row);
-                xk = *(const u32x4 *)(k_new + row);
-                xv = *(const u32x4 *)(v_new + row);
-            }
-            xbid = trow[L / kBlockTokens];
-        }
+        const int j_cur = j, h_cur = h, k_cur = k, L_cur = L, NB_cur = NB;
 
         // ---- scores of this unit's 64 tokens (base 2: scale*log2(e) folded in) ----
         float sc;
@@ -444,31 +438,17 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         if (last_of_range) FS_TRACE_STAMP(4);
 #endif
 
-        // ---- values of this unit's four blocks ----
-#pragma unroll
-        for (int b = 0; b < kStepBlocks; ++b) {
-            const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
-            int bi = kStepBlocks * k + b;
-            bi = bi < NB ? bi : NB - 1;
-            if (kFused) bi = bi > 0 ? bi : 0;
-            const int left = L - bi * kBlockTokens;  // valid slots of that block (>= 1 unless the cache is empty)
-            const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + h) * kChunkBytes + (size_t)vc * 16;
-            // fused, empty cache: nothing of this job is in the pool yet; the loads read the
-            // job's own new value row instead (finite data, weight zero), slot 0 below
-            if (kFused && L == 0) vp = v_new + ((size_t)j * H + h) * kRowBytes + (size_t)vc * 16;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                int slot = i * TPI + vt;
-                slot = slot < left ? slot : left - 1;
-                if (kFused) slot = slot > 0 ? slot : 0;
-                vr[b][i] = *(const u32x4 *)(vp + (size_t)slot * kRowBytes);
-            }
-        }
-
-        // ---- the next unit: its q and keys go in flight now ----
+        // ---- which unit comes next.  Done here, with nothing of this unit in flight yet:
+        // the rare table reloads below wait for their own data only ----
         if (!last_of_range) {
             if (!last_of_pair) {
                 ++k;
+                if (k - kt == kWindowSteps) {  // walk on to the next 128 table entries
+                    kt = k;
+                    int w0, w1;
+                    fetch_window(trow, kt, w0, w1);
+                    store_window(w0, w1);
+                }
             } else {
                 k = 0;
                 if (++h == H) {  // next job: its length and first table window are already here
@@ -478,30 +458,65 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                     steps = steps_of(L);
                     NB = (L + kBlockTokens - 1) / kBlockTokens;
                     trow = table + (size_t)j * sh.table_stride;
-                    tbl = ntbl;
-                    tbl_nx = ntbl_nx;
                     kt = 0;
+                    store_window(ntbl, ntbl_nx);
                     nj = next_job(j);
                     if (nj < J) {
                         nL = __builtin_amdgcn_readfirstlane(s_len[nj]);
-                        load_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
+                        fetch_window(table + (size_t)nj * sh.table_stride, 0, ntbl, ntbl_nx);
                     }
                 } else if (kt != 0) {  // same job, next head: back to the first table window
                     kt = 0;
-                    load_window(trow, 0, tbl, tbl_nx);
+                    int w0, w1;
+                    fetch_window(trow, 0, w0, w1);
+                    store_window(w0, w1);
                 }
             }
         }
+        const int bid_next = row_block(k);
+
+        // ---- values of this unit's four blocks ----
+#pragma unroll
+        for (int b = 0; b < kStepBlocks; ++b) {
+            const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
+            int bi = kStepBlocks * k_cur + b;
+            bi = bi < NB_cur ? bi : NB_cur - 1;
+            if (kFused) bi = bi > 0 ? bi : 0;
+            const int left = L_cur - bi * kBlockTokens;  // valid slots of that block (>= 1 unless the cache is empty)
+            const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + h_cur) * kChunkBytes + (size_t)vc * 16;
+            // fused, empty cache: nothing of this job is in the pool yet; the loads read the
+            // job's own new value row instead (finite data, weight zero), slot 0 below
+            if (kFused && L_cur == 0) vp = v_new + ((size_t)j_cur * H + h_cur) * kRowBytes + (size_t)vc * 16;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                int slot = i * TPI + vt;
+                slot = slot < left ? slot : left - 1;
+                if (kFused) slot = slot > 0 ? slot : 0;
+                vr[b][i] = *(const u32x4 *)(vp + (size_t)slot * kRowBytes);
+            }
+        }
+        if (kFused && last_of_pair) {
+            // the new token's vectors and the block it goes to: asked for now, used at the pair's end
+            const size_t row = ((size_t)j_cur * H + h_cur) * kRowBytes + (size_t)vc * 16;
+            if (lane < LPT) {
+                xq = *(const u32x4 *)((const char *)q + row);
+                xk = *(const u32x4 *)(k_new + row);
+                xv = *(const u32x4 *)(v_new + row);
+            }
+            xbid = table[(size_t)j_cur * sh.table_stride + L_cur / kBlockTokens];
+        }
+
+        // ---- the next unit's q and keys go in flight ----
         // (the range's last unit has no successor: its loads are pointed at the first
         // 4 KiB of the pool, one hot set of lines for every wave, instead of a branch)
         load_q(j, h);
-        bid = row_block(k);
         {
-            const char *kp = pool + (size_t)bid * block_bytes + (size_t)h * kChunkBytes + (size_t)s * 16;
+            const char *kp = pool + (size_t)bid_next * block_bytes + (size_t)h * kChunkBytes + (size_t)s * 16;
             kp = last_of_range ? pool + (size_t)s * 16 : kp;
 #pragma unroll
             for (int i = 0; i < NK; ++i) kr[i] = *(const u32x4 *)(kp + i * (kBlockTokens * 16));
         }
+        bid = bid_next;
 
         // ---- online softmax; the weights reach the value lanes through LDS ----
         {
