@@ -185,7 +185,7 @@ def cpu_baseline(reps, budget_s=12.0):
         return lc
 
     times, out, spent = [], None, 0.0
-    while spent < budget_s and len(times) < 50:
+    while spent < budget_s and len(times) < 200:
         lc = fresh()
         t0 = time.perf_counter()
         out = lc.decode_step(k_new, v_new, step.q)
