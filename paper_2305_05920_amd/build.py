@@ -8,7 +8,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "fastserve.hip")
+SOURCES = [os.path.join(HERE, "csrc", "fastserve.hip"), os.path.join(HERE, "csrc", "serving.cpp")]
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(HERE, "libfastserve.so")
 
@@ -32,7 +32,7 @@ def hipcc_path() -> str:
 
 def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     tmp = out + f".tmp{os.getpid()}"
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, SRC, "-o", tmp,
+    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, *SOURCES, "-o", tmp,
            "-Wl,-rpath,/opt/rocm/lib"]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "fastserve.h")
+HEADERS = [os.path.join(ROOT, "include", "fastserve.h"), os.path.join(ROOT, "include", "fastserve_sched.h")]
 
 
 @pytest.fixture(scope="module")
@@ -21,7 +21,7 @@ def fs():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(fs_[a-z_0-9]+)\s*\(", text)))
 
@@ -32,7 +32,8 @@ def test_every_declared_function_is_exported(fs):
     lib = fs.load_library()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
-    assert sorted(fs.EXPORTS) == names, "binding and header disagree on the entry points"
+    from paper_2305_05920_amd import sched
+    assert sorted(fs.EXPORTS + sched.SCHED_EXPORTS) == names, "binding and headers disagree on the entry points"
 
 
 def test_status_strings_and_version(fs):
