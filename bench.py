@@ -42,6 +42,8 @@ def algorithmic_bytes(cfg, lens) -> int:
 class Replicas:
     """R copies of one workload's pool in HBM, each behind its own fs_pool."""
 
+    SWAP_BLOCKS = 8   # most blocks moved each way per step in the swap-overlap measurement
+
     def __init__(self, fs, torch, wl, cfg, rep, min_footprint_bytes, pool_kw, log):
         self.fs, self.torch, self.cfg = fs, torch, cfg
         step = wl.make_step(cfg, rep)
@@ -55,9 +57,13 @@ class Replicas:
         R = min(R, max(2, int(24e9 // pool_bytes)))
         self.R = R
         tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-        self.mem = torch.empty((R, bt.num_blocks, block_elems), dtype=tdt, device="cuda")
-        self.pools = [fs.Pool(cfg.dtype, H, D, bt.num_blocks, device_mem=self.mem[r], **pool_kw)
-                      for r in range(R)]
+        # SWAP_BLOCKS extra blocks at the end of each pool: a waiting job's blocks that
+        # travel to the host and back while the batch runs (swap-overlap measurement)
+        nb_all = bt.num_blocks + self.SWAP_BLOCKS
+        self.mem = torch.empty((R, nb_all, block_elems), dtype=tdt, device="cuda")
+        self.pools = [fs.Pool(cfg.dtype, H, D, nb_all, device_mem=self.mem[r],
+                              num_host_blocks=self.SWAP_BLOCKS, **pool_kw) for r in range(R)]
+        self.spare_blocks = np.arange(bt.num_blocks, nb_all, dtype=np.int32)
         self.table = torch.from_numpy(bt.table).cuda()
         self.lens = torch.from_numpy(step.lens).cuda()
         lens_before = (step.lens - 1).astype(np.int32)
@@ -117,6 +123,39 @@ class Replicas:
     def close(self):
         for p in self.pools:
             p.close()
+
+
+def swap_overlap(torch, reps, steps, warmup):
+    """Steps with block traffic to and from pinned host memory on a side stream (the
+    paper's proactive swapping, Section 4.2): every step, SWAP_BLOCKS blocks that no
+    running job uses leave for host slots and come back."""
+    fs = reps.fs
+    block_bytes = reps.pools[0].block_bytes
+    # traffic sized to about 12 GB/s each way at the step's expected duration, i.e. well
+    # inside what the host link sustains (measured here: ~37 GB/s both ways together)
+    est_step_s = reps.alg_bytes / 5.5e12 + 15e-6
+    n = int(min(len(reps.spare_blocks), max(1, 12e9 * est_step_s // block_bytes)))
+    ids = reps.spare_blocks[:n]
+    slots = np.arange(len(ids), dtype=np.int32)
+    side = torch.cuda.Stream()
+
+    def run(n, first):
+        for i in range(n):
+            pool = reps.pools[(first + i) % reps.R]
+            fs.fs_pool_offload(pool, ids, slots, stream=side)
+            fs.fs_pool_upload(pool, slots, ids, stream=side)
+            reps.run_step(first + i)
+    run(warmup, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps, warmup)
+    torch.cuda.current_stream().synchronize()
+    t_compute = time.perf_counter() - t0
+    side.synchronize()
+    t_all = time.perf_counter() - t0
+    return {"blocks_each_way_per_step": int(len(ids)), "block_bytes": int(block_bytes),
+            "ms_per_step_compute_stream": t_compute * 1e3 / steps, "ms_per_step_until_copies_done": t_all * 1e3 / steps,
+            "host_link_gbps": 2 * len(ids) * block_bytes * steps / t_all / 1e9}
 
 
 def time_steps(torch, reps, steps, warmup):
@@ -278,6 +317,7 @@ def main():
                    "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
                                   "kernel_ms": kt_f,
                                   "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
+            res["swap_overlap"] = swap_overlap(torch, reps, max(50, steps // 2), max(5, warmup // 2))
             if not args.no_graph:
                 try:
                     res["ms_per_step_graph"] = graph_ms(torch, reps, steps)
@@ -334,6 +374,7 @@ def main():
         "cpu_baseline": base,
         "kernel_ms": main_res["kernel_ms"],
         "fused_step": main_res["fused_step"],
+        "swap_overlap": main_res.get("swap_overlap"),
         "ms_per_step_graph": main_res.get("ms_per_step_graph"),
         "max_abs_err": main_res.get("max_abs_err"),
         "rel_l2_err": main_res.get("rel_l2_err"),

@@ -167,7 +167,12 @@ int fs_decode_step(fs_pool *pool, const int32_t *block_table, int32_t table_stri
  *      swapped out to host memory and swapped in before the job is scheduled) --------
  * Copies n whole blocks between pool blocks block_ids[i] and pinned host slots
  * host_slots[i] (host int32 arrays, read before return), asynchronously on
- * `stream`.  Upload may target any block id; the caller patches its tables. */
+ * `stream`.  Upload may target any block id; the caller patches its tables.
+ * By default each run of consecutive (block id, host slot) pairs is one
+ * hipMemcpyAsync on the copy engines, which leaves the compute units to a decode
+ * step running on another stream; knob "swap_engine" = 1 selects a copy kernel
+ * instead (up to 32 blocks per launch, the GPU accessing the pinned host memory
+ * directly), faster per block but in competition with a concurrent decode step. */
 int fs_pool_offload(fs_pool *pool, const int32_t *block_ids, const int32_t *host_slots,
                     int32_t n, void *stream);
 int fs_pool_upload(fs_pool *pool, const int32_t *host_slots, const int32_t *block_ids,
@@ -191,7 +196,8 @@ int fs_profile_enable(fs_pool *pool, int32_t enable);
 int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
 
 /* Named integer knobs for sweeps: "wgs_per_cu" (persistent attention workgroups per
- * compute unit, 1..8) and "max_workgroups" (cap on that grid, 0 = none); readable
+ * compute unit, 1..8), "max_workgroups" (cap on that grid, 0 = none) and "swap_engine"
+ * (see fs_pool_offload); readable
  * also: "num_cus", "max_jobs_per_launch".  Unknown name or out-of-range value ->
  * FS_ERR_INVALID_ARG. */
 int fs_pool_set_param(fs_pool *pool, const char *name, int32_t value);

@@ -1,0 +1,144 @@
+"""Proactive key-value cache manager (FastServe, Section 4.2) on top of the block pool.
+
+Host-side bookkeeping only: which job owns which pool blocks, which jobs sit in the
+pinned host mirror, and in which order jobs move (the ENST order of the scheduler).
+The copies themselves are the library's ``fs_pool_offload`` / ``fs_pool_upload`` on a
+side stream, so that the transfer of waiting jobs overlaps the decode kernels of the
+running batch; the decode kernels see nothing of this but the block table.
+
+Blocks are owned by jobs in whole; a job is either resident (all its blocks in HBM) or
+swapped out (all its blocks in host slots).  ``reserve_idle_blocks`` HBM blocks are
+kept free for new arrivals (Section 4.2, "Handling a burst of new jobs").
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import Pool, fs_pool_offload, fs_pool_upload
+from .sched import Scheduler
+
+
+@dataclass
+class JobBlocks:
+    length: int = 0                                         # tokens cached
+    blocks: List[int] = field(default_factory=list)         # pool block ids (when resident)
+    host_slots: List[int] = field(default_factory=list)     # host slots (when swapped out)
+    resident: bool = True
+
+
+class KVManager:
+    def __init__(self, pool: Pool, sched: Scheduler, table_width: int, reserve_idle_blocks: int = 0):
+        self.pool, self.sched = pool, sched
+        self.B = pool.block_size
+        self.W = table_width
+        self.reserve = reserve_idle_blocks
+        self.free_blocks: List[int] = list(range(pool.num_blocks - 1, -1, -1))
+        self.free_slots: List[int] = list(range(pool.num_host_blocks - 1, -1, -1))
+        self.jobs: Dict[int, JobBlocks] = {}
+        self.side = torch.cuda.Stream()
+        self.swapped_out_blocks = 0      # statistics
+        self.swapped_in_blocks = 0
+
+    # -- allocation ---------------------------------------------------------------------
+    def blocks_needed(self, tokens: int) -> int:
+        return (tokens + self.B - 1) // self.B
+
+    def can_admit(self, tokens: int) -> bool:
+        return self.blocks_needed(tokens) <= len(self.free_blocks)
+
+    def admit(self, job_id: int, tokens: int) -> None:
+        """Allocate blocks for a new job's `tokens` tokens (its prompt)."""
+        n = self.blocks_needed(tokens)
+        if n > len(self.free_blocks) or n > self.W:
+            raise MemoryError("no room for the job")
+        self.jobs[job_id] = JobBlocks(length=0, blocks=[self.free_blocks.pop() for _ in range(n)])
+
+    def grow(self, job_id: int, new_tokens: int = 1) -> bool:
+        """Make room for `new_tokens` more tokens of a resident job; False if HBM is full."""
+        jb = self.jobs[job_id]
+        need = self.blocks_needed(jb.length + new_tokens) - len(jb.blocks)
+        if need > len(self.free_blocks) or len(jb.blocks) + need > self.W:
+            return False
+        for _ in range(need):
+            jb.blocks.append(self.free_blocks.pop())
+        return True
+
+    def advance(self, job_id: int, tokens: int = 1) -> None:
+        self.jobs[job_id].length += tokens
+
+    def release(self, job_id: int) -> None:
+        jb = self.jobs.pop(job_id)
+        self.free_blocks.extend(jb.blocks)
+        self.free_slots.extend(jb.host_slots)
+
+    def table_rows(self, job_ids: Sequence[int]) -> np.ndarray:
+        t = np.full((len(job_ids), self.W), -1, dtype=np.int32)
+        for r, j in enumerate(job_ids):
+            b = self.jobs[j].blocks
+            t[r, :len(b)] = b
+        return t
+
+    # -- swapping -----------------------------------------------------------------------
+    def _offload(self, job_id: int) -> None:
+        jb = self.jobs[job_id]
+        slots = [self.free_slots.pop() for _ in jb.blocks]
+        fs_pool_offload(self.pool, jb.blocks, slots, stream=self.side)
+        self.swapped_out_blocks += len(slots)
+        self._pending_free.extend(jb.blocks)      # reusable once the copy has run
+        jb.host_slots, jb.blocks, jb.resident = slots, [], False
+        self.sched.set_ready(job_id, False)
+
+    def _upload(self, job_id: int) -> None:
+        jb = self.jobs[job_id]
+        blocks = [self.free_blocks.pop() for _ in jb.host_slots]
+        fs_pool_upload(self.pool, jb.host_slots, blocks, stream=self.side)
+        self.swapped_in_blocks += len(blocks)
+        self._pending_slots.extend(jb.host_slots)
+        self._pending_ready.append(job_id)         # schedulable once the copy has run
+        jb.blocks, jb.host_slots, jb.resident = blocks, [], True
+
+    def start_swaps(self, running: Sequence[int], want_free: int = 0) -> None:
+        """Issue this iteration's swaps on the side stream (they overlap the decode step
+        of `running`, which the caller launches next on its own stream).
+
+        Swap out, largest ENST first, resident jobs that are not running until
+        `reserve_idle_blocks + want_free` blocks are free (counting blocks whose offload
+        is in flight); then swap in, smallest ENST first, jobs whose return leaves that
+        margin intact."""
+        self._pending_free: List[int] = []
+        self._pending_slots: List[int] = []
+        self._pending_ready: List[int] = []
+        # the copies must see everything the compute stream has written so far
+        self.side.wait_stream(torch.cuda.current_stream())
+        margin = self.reserve + want_free
+        running = set(running)
+        out_cand = [j for j, jb in self.jobs.items() if jb.resident and j not in running and jb.blocks]
+        free_after = len(self.free_blocks)
+        for j in self.sched.swap_order(out_cand, swap_in=False):
+            if free_after >= margin:
+                break
+            if len(self.jobs[j].blocks) > len(self.free_slots):
+                continue
+            free_after += len(self.jobs[j].blocks)
+            self._offload(j)
+        in_cand = [j for j, jb in self.jobs.items() if not jb.resident]
+        for j in self.sched.swap_order(in_cand, swap_in=True):
+            n = len(self.jobs[j].host_slots)
+            if len(self.free_blocks) - n < margin:
+                break
+            self._upload(j)
+
+    def finish_swaps(self) -> None:
+        """Wait for the side stream; blocks and slots vacated by the copies become free
+        and uploaded jobs become schedulable."""
+        self.side.synchronize()
+        self.free_blocks.extend(self._pending_free)
+        self.free_slots.extend(self._pending_slots)
+        for j in self._pending_ready:
+            if j in self.jobs:
+                self.sched.set_ready(j, True)
+        self._pending_free, self._pending_slots, self._pending_ready = [], [], []

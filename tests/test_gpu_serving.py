@@ -1,0 +1,111 @@
+"""Token-granularity preemptive serving end to end on the GPU: the skip-join MLFQ
+scheduler admits a different ragged batch every iteration, the proactive cache manager
+moves the blocks of waiting jobs to host memory and back on a side stream while the
+decode step of the running batch executes, and every generated token's attention output
+is checked against the CPU oracle's logical caches (which know nothing of blocks,
+preemption or swapping)."""
+import numpy as np
+import pytest
+import torch
+
+import fs_workload as wl
+import oracle
+from tests import harness as hs
+
+pytestmark = pytest.mark.gpu
+
+
+def test_serving_loop_with_preemption_and_swapping_matches_oracle():
+    import paper_2305_05920_amd as fs
+    from paper_2305_05920_amd.kv_manager import KVManager
+    from paper_2305_05920_amd.sched import Scheduler
+
+    H, D, W = 4, 128, 16                       # up to 256 tokens per job
+    cfg = wl.CONFIGS[1].scaled(num_heads=H, head_dim=D)
+    rng = np.random.default_rng(2305)
+    njobs = 16
+    prompts = rng.integers(20, 150, size=njobs)
+    outputs = rng.integers(3, 12, size=njobs)
+    arrival = np.sort(rng.integers(0, 12, size=njobs))
+    # HBM pool of 36 blocks (576 tokens) for ~1800 tokens of live cache: swapping is forced
+    pool = fs.Pool("bf16", H, D, 36, num_host_blocks=160)
+    sched = Scheduler(4, 1.0, 1, 6.0, 4)
+    kv = KVManager(pool, sched, W, reserve_idle_blocks=4)
+
+    def rand_bits(shape):
+        return wl.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+
+    K = {j: np.zeros((256, H, D), np.uint16) for j in range(njobs)}      # logical caches (oracle side)
+    V = {j: np.zeros((256, H, D), np.uint16) for j in range(njobs)}
+    length = {j: 0 for j in range(njobs)}
+    produced = {j: 0 for j in range(njobs)}
+    waiting, done = [], set()
+    last_ran, preempted = {}, set()
+    checked = 0
+    it = 0
+    while len(done) < njobs:
+        assert it < 600, "serving loop does not terminate"
+        waiting += [j for j in range(njobs) if arrival[j] == it]
+        for j in list(waiting):                                  # admission: prompt must fit beside the reserve
+            if kv.blocks_needed(int(prompts[j]) + 1) + kv.reserve <= len(kv.free_blocks):
+                kv.admit(j, int(prompts[j]) + 1)
+                sched.add_job(j, float(prompts[j]) / 32.0, 1.0)
+                waiting.remove(j)
+        batch = [j for j in sched.schedule()]
+        # a decoding job needs room for one more token; if HBM is full it sits this one out
+        runnable = [j for j in batch if length[j] == 0 or kv.grow(j, 1)]
+        kv.start_swaps(runnable, want_free=len(batch) - len(runnable) + len(waiting))
+        first = [j for j in runnable if length[j] == 0]
+        decode = [j for j in runnable if length[j] > 0]
+        for j in first:                                          # initialization phase: the prompt's KV
+            n = int(prompts[j])
+            K[j][:n], V[j][:n] = rand_bits((n, H, D)), rand_bits((n, H, D))
+            fs.fs_kv_prefill(pool, torch.from_numpy(kv.table_rows([j])).cuda(),
+                             torch.zeros(1, dtype=torch.int32, device="cuda"),
+                             torch.tensor([0, n], dtype=torch.int32, device="cuda"), n,
+                             hs.to_torch("bf16", K[j][:n]), hs.to_torch("bf16", V[j][:n]))
+            kv.advance(j, n)
+            length[j] = n
+        if decode:                                               # decoding phase: one fused step
+            q, kn, vn = (rand_bits((len(decode), H, D)) for _ in range(3))
+            lens_before = np.array([length[j] for j in decode], dtype=np.int32)
+            out = torch.full((len(decode), H, D), float("nan"), dtype=torch.float32, device="cuda")
+            fs.fs_decode_step(pool, torch.from_numpy(kv.table_rows(decode)).cuda(),
+                              torch.from_numpy(lens_before).cuda(), hs.to_torch("bf16", kn),
+                              hs.to_torch("bf16", vn), hs.to_torch("bf16", q), out)
+        kv.finish_swaps()
+        torch.cuda.synchronize()
+        pool.check()
+        if decode:
+            got = out.cpu().numpy()
+            for r, j in enumerate(decode):
+                K[j][length[j]], V[j][length[j]] = kn[r], vn[r]
+                length[j] += 1
+                kv.advance(j, 1)
+                ref = oracle.attention_job(q[r], K[j], V[j], "bf16", length=length[j])
+                hs.assert_parity(got[r], ref, f"iteration {it} job {j} length {length[j]}") if checked % 25 == 0 else None
+                err = np.abs(got[r] - ref).max()
+                assert err <= hs.MAX_ABS_TOL, (it, j, err)
+                checked += 1
+        finished = []
+        for j in runnable:
+            produced[j] += 1
+            if j in last_ran and last_ran[j] < it - 1:
+                preempted.add(j)                                  # it waited while others ran
+            last_ran[j] = it
+            if produced[j] == outputs[j]:
+                finished.append(j)
+        elapsed = max([float(prompts[j]) / 32.0 if j in first else 1.0 for j in runnable], default=1.0)
+        sched.complete_iteration(runnable, elapsed, finished)
+        for j in finished:
+            kv.release(j)
+            done.add(j)
+        it += 1
+    print(f"[serving] {it} iterations, {checked} decode outputs checked, {len(preempted)} jobs preempted, "
+          f"{kv.swapped_out_blocks} blocks swapped out, {kv.swapped_in_blocks} swapped in", flush=True)
+    assert checked == int((outputs - 1).sum())
+    assert kv.swapped_out_blocks > 0 and kv.swapped_in_blocks > 0, "the test did not exercise swapping"
+    assert preempted, "no job was ever preempted"
+    assert len(kv.free_blocks) == pool.num_blocks and len(kv.free_slots) == pool.num_host_blocks
+    sched.close()
+    pool.close()
