@@ -188,7 +188,8 @@ typedef enum fs_kernel_kind {
     FS_KERNEL_KINDS = 4
 } fs_kernel_kind;
 
-/* While enabled, every kernel launch is bracketed by HIP events on its stream. */
+/* While enabled, every kernel launch carries a pair of HIP events on its stream that the
+ * runtime stamps with the kernel's own start and end. */
 int fs_profile_enable(fs_pool *pool, int32_t enable);
 /* Waits for the recorded events; adds up milliseconds and launch counts per
  * fs_kernel_kind into total_ms[FS_KERNEL_KINDS], launches[FS_KERNEL_KINDS]

@@ -25,6 +25,7 @@
 //    grid is persistent: every wave strides over the items.
 //  * The path is a batched GEMV at 1 flop/byte: HBM-bound, no MFMA.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdio>
@@ -904,29 +905,32 @@ int alloc_scratch(fs_pool *p) {
     return FS_OK;
 }
 
-struct ProfileScope {
-    fs_pool *p;
-    hipStream_t s;
-    ProfileRecord rec{};
-    bool on;
-    ProfileScope(fs_pool *pool, int kind, hipStream_t stream) : p(pool), s(stream), on(pool->profiling) {
-        if (!on) return;
+// Launches a kernel; while profiling is on, the launch carries a HIP event pair that the
+// runtime stamps with the kernel's own start and end (the same span a profiler reports
+// for the dispatch), on the stream the kernel runs on.
+template <typename... Params, typename... Args>
+void launch_kernel(fs_pool *p, int kind, void (*kernel)(Params...), dim3 grid, hipStream_t s, Args... args)
+{
+    if (p->profiling) {
+        ProfileRecord rec{};
+        bool have = false;
         if (!p->spare.empty()) {
             rec = p->spare.back();
             p->spare.pop_back();
-        } else if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) {
-            on = false;
+            have = true;
+        } else if (hipEventCreate(&rec.start) == hipSuccess) {
+            if (hipEventCreate(&rec.stop) == hipSuccess) have = true;
+            else (void)hipEventDestroy(rec.start);
+        }
+        if (have) {
+            rec.kind = kind;
+            hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, s, rec.start, rec.stop, 0, static_cast<Params>(args)...);
+            p->records.push_back(rec);
             return;
         }
-        rec.kind = kind;
-        (void)hipEventRecord(rec.start, s);
     }
-    ~ProfileScope() {
-        if (!on) return;
-        (void)hipEventRecord(rec.stop, s);
-        p->records.push_back(rec);
-    }
-};
+    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, s, static_cast<Params>(args)...);
+}
 
 template <typename E, int D, bool kFused>
 int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v_new, const int32_t *table,
@@ -946,25 +950,19 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
     if (wgs < 1) wgs = 1;
     if (wgs * kWavesPerWg > p->waves_cap) return FS_ERR_INVALID_ARG;
-    {
-        ProfileScope ps(p, FS_KERNEL_ATTENTION, s);
-        hipLaunchKernelGGL((fs_attn_partition_kernel<E, D, kFused>), dim3((unsigned)wgs), dim3(kThreads), 0, s,
-                           (const uint32_t *)q, (const char *)p->mem, kFused ? p->mem : (char *)nullptr,
-                           (const char *)k_new, (const char *)v_new, table, lens, out, p->part_acc,
-                           p->part_ml, p->plan, p->err, sh
+    launch_kernel(p, FS_KERNEL_ATTENTION, fs_attn_partition_kernel<E, D, kFused>, dim3((unsigned)wgs), s,
+                  (const uint32_t *)q, (const char *)p->mem, kFused ? p->mem : (char *)nullptr,
+                  (const char *)k_new, (const char *)v_new, table, lens, out, p->part_acc, p->part_ml, p->plan,
+                  p->err, sh
 #ifdef FS_TRACE
-                           , p->trace
+                  , p->trace
 #endif
-                           );
-    }
+    );
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
-    {
-        ProfileScope ps(p, FS_KERNEL_COMBINE, s);
-        const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
-        hipLaunchKernelGGL((fs_attn_combine_kernel<D>), dim3((unsigned)cw), dim3(kThreads), 0, s,
-                           (const float *)p->part_acc, (const float *)p->part_ml,
-                           (const int32_t *)p->plan, out, J, sh.num_heads, (int32_t)(wgs * kWavesPerWg));
-    }
+    const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
+    launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_kernel<D>, dim3((unsigned)cw), s,
+                  (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
+                  sh.num_heads, (int32_t)(wgs * kWavesPerWg));
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     return FS_OK;
 }
@@ -1109,15 +1107,12 @@ int fs_kv_append(fs_pool *p, const int32_t *table, int32_t stride, const int32_t
     const long long vecs = (long long)J * H * (D * p->elem_bytes / 16);
     const long long wgs = (vecs + kThreads - 1) / kThreads;
     if (wgs > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
-    {
-        ProfileScope ps(p, FS_KERNEL_APPEND, s);
-        if (p->elem_bytes == 2)
-            hipLaunchKernelGGL((fs_kv_append_kernel<2>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
-                               stride, lens, J, H, D, p->cfg.num_blocks, (const char *)k, (const char *)v, p->err);
-        else
-            hipLaunchKernelGGL((fs_kv_append_kernel<4>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
-                               stride, lens, J, H, D, p->cfg.num_blocks, (const char *)k, (const char *)v, p->err);
-    }
+    if (p->elem_bytes == 2)
+        launch_kernel(p, FS_KERNEL_APPEND, fs_kv_append_kernel<2>, dim3((unsigned)wgs), s, p->mem, table, stride, lens,
+                      J, H, D, p->cfg.num_blocks, (const char *)k, (const char *)v, p->err);
+    else
+        launch_kernel(p, FS_KERNEL_APPEND, fs_kv_append_kernel<4>, dim3((unsigned)wgs), s, p->mem, table, stride, lens,
+                      J, H, D, p->cfg.num_blocks, (const char *)k, (const char *)v, p->err);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
@@ -1134,17 +1129,14 @@ int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_
     const long long vecs = (long long)total_tokens * H * (D * p->elem_bytes / 16);
     const long long wgs = (vecs + kThreads - 1) / kThreads;
     if (wgs > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
-    {
-        ProfileScope ps(p, FS_KERNEL_PREFILL, s);
-        if (p->elem_bytes == 2)
-            hipLaunchKernelGGL((fs_kv_prefill_kernel<2>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
-                               stride, starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens,
-                               (const char *)k, (const char *)v, p->err);
-        else
-            hipLaunchKernelGGL((fs_kv_prefill_kernel<4>), dim3((unsigned)wgs), dim3(kThreads), 0, s, p->mem, table,
-                               stride, starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens,
-                               (const char *)k, (const char *)v, p->err);
-    }
+    if (p->elem_bytes == 2)
+        launch_kernel(p, FS_KERNEL_PREFILL, fs_kv_prefill_kernel<2>, dim3((unsigned)wgs), s, p->mem, table, stride,
+                      starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, (const char *)k,
+                      (const char *)v, p->err);
+    else
+        launch_kernel(p, FS_KERNEL_PREFILL, fs_kv_prefill_kernel<4>, dim3((unsigned)wgs), s, p->mem, table, stride,
+                      starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, (const char *)k,
+                      (const char *)v, p->err);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 

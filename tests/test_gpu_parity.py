@@ -334,6 +334,41 @@ def test_widest_table_of_the_long_context_preset():
     hs.assert_parity(got, hs.oracle_step(case), "max length")
 
 
+# ---- seeded random shapes --------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(6))
+def test_random_batches_grids_and_entry_points(seed):
+    # random job counts, head counts, head_dim, dtype, length mixes (zeros included for the
+    # two-call form) and grid caps; both entry points against the oracle
+    rng = np.random.default_rng(1000 + seed)
+    D = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "f32"]))
+    H = int(rng.integers(1, 9))
+    J = int(rng.integers(1, 40))
+    mix = rng.choice(["short", "long", "mixed"])
+    hi = {"short": 80, "long": 1500, "mixed": 700}[mix]
+    lens = rng.integers(1, hi, size=J)
+    if mix == "mixed":
+        short = rng.random(J) < 0.5
+        lens = np.where(short, rng.integers(1, 20, size=J), lens)
+    cfg = wl.CONFIGS[1].scaled(num_jobs=J, num_heads=H, head_dim=D, dtype=dtype, max_len=1536)
+    case = hs.make_case(cfg, seed, lens=lens)
+    wgs = int(rng.choice([0, 1, 3, 17, 200]))
+    print(f"[case] random seed {seed}: J={J} H={H} D={D} {dtype} mix={mix} max_workgroups={wgs}", flush=True)
+    ref = hs.oracle_step(case)
+    a = hs.DeviceRun(case, max_workgroups=wgs)
+    b = hs.DeviceRun(case, max_workgroups=wgs)
+    try:
+        a.append()
+        two = a.attention(max_len_hint=int(lens.max()))
+        one = b.fused_step(max_len_hint=int(lens.max()))
+        a.pool.check(), b.pool.check()
+        assert np.array_equal(a.image().view(np.uint8), b.image().view(np.uint8))
+    finally:
+        a.close(), b.close()
+    hs.assert_parity(two, ref, f"random {seed} two-call")
+    hs.assert_parity(one, ref, f"random {seed} fused")
+
+
 # ---- offload / upload ----------------------------------------------------------------
 def test_offload_upload_round_trip_and_bitwise_stable_attention():
     # preset 2's recipe: a quarter of the jobs leave for host slots and return under
