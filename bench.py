@@ -270,8 +270,8 @@ def main():
                     help="also launch the plain stream read/copy kernels over 1 GiB (scale of hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by head with no exchange; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path shards by head, with no exchange "
+              "between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch

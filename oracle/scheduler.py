@@ -11,8 +11,12 @@ MaxBatchSize ready jobs in priority order.
 Swap order: paper Section 4.2, "Job swapping order": ENST(i) =
 min(T_promote(i), T_execute(i)).
 
-Where the paper leaves room, this file takes the readings listed in the design doc
-(section "Readings: scheduler").
+Where the paper leaves room, this file takes these readings: a job that ran is charged
+the iteration's elapsed time; a demoted job moves eta queues down, further if its next
+iteration would not fit that quantum; waiting time counts from the last run, arrival or
+promotion; jobs are visited Q_1 first, first-in first-out inside a queue; in the ENST sum
+a job j of a higher-priority queue passes the quanta of its own queue and of every queue
+between it and job i's queue.
 """
 from __future__ import annotations
 
