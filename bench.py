@@ -56,7 +56,7 @@ class Replicas:
         R = max(2, int(np.ceil(min_footprint_bytes / max(self.alg_bytes, 1))))
         R = min(R, max(2, int(24e9 // pool_bytes)))
         self.R = R
-        tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[cfg.dtype]
         # SWAP_BLOCKS extra blocks at the end of each pool: a waiting job's blocks that
         # travel to the host and back while the batch runs (swap-overlap measurement)
         nb_all = bt.num_blocks + self.SWAP_BLOCKS
@@ -104,8 +104,9 @@ class Replicas:
 
     def _dev(self, a):
         t = self.torch
-        if self.cfg.dtype == "bf16":
-            return t.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(t.bfloat16)
+        if self.cfg.dtype in ("bf16", "f16"):
+            return t.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(
+                t.bfloat16 if self.cfg.dtype == "bf16" else t.float16)
         return t.from_numpy(np.ascontiguousarray(a)).cuda()
 
     fused = False
@@ -261,6 +262,8 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=1, help="workload preset timed as the headline (default 1)")
+    ap.add_argument("--dtype", type=str, default="", choices=["", "bf16", "f16", "f32"],
+                    help="override the presets' storage type (default: the preset's own, bf16)")
     ap.add_argument("--also", type=str, default="2,3,4", help="other presets reported under 'other_workloads'")
     ap.add_argument("--footprint-gb", type=float, default=2.0, help="bytes touched between reuses of a replica")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
@@ -299,7 +302,7 @@ def main():
         del src, dst
 
     def measure(idx, steps, warmup, with_cpu):
-        cfg = wl.CONFIGS[idx]
+        cfg = wl.CONFIGS[idx] if not args.dtype else wl.CONFIGS[idx].scaled(dtype=args.dtype)
         reps = Replicas(fs, torch, wl, cfg, 0, args.footprint_gb * 1e9, pool_kw, log)
         try:
             if args.wgs_per_cu:
@@ -347,7 +350,7 @@ def main():
         r, _ = measure(idx, max(50, args.steps // 4), max(10, args.warmup // 4), False)
         others.append(r)
 
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.CONFIGS[args.config] if not args.dtype else wl.CONFIGS[args.config].scaled(dtype=args.dtype)
     attn_ms = main_res["kernel_ms"]["attention"]
     achieved = main_res["alg_bytes"] / (attn_ms * 1e-3) / 1e9
     line = {

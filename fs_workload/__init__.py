@@ -11,7 +11,7 @@ OPT-13B 40 heads / hidden 5120, OPT-175B 96 heads / hidden 12288, so
 head_dim 128) and its description of serving workloads as long-tailed and
 skewed (Section 2.3, Figure 1); the datasets themselves are not used.
 
-Storage convention: bf16 tensors are carried as numpy ``uint16`` bit patterns
+Storage convention: bf16 and f16 tensors are carried as numpy ``uint16`` bit patterns
 (round-to-nearest-even of an fp32 N(0,1) draw, done once here), fp32 tensors as
 ``float32``.
 """
@@ -36,7 +36,7 @@ class WorkloadConfig:
     name: str
     num_heads: int
     head_dim: int
-    dtype: str          # "bf16" or "f32"
+    dtype: str          # "bf16", "f16" or "f32"
     num_jobs: int
     lens_recipe: str    # see job_lens()
     table_recipe: str   # see block_tables()
@@ -45,11 +45,11 @@ class WorkloadConfig:
 
     @property
     def elem_bytes(self) -> int:
-        return 2 if self.dtype == "bf16" else 4
+        return 2 if self.dtype in ("bf16", "f16") else 4
 
     @property
     def np_dtype(self):
-        return np.uint16 if self.dtype == "bf16" else np.float32
+        return np.uint16 if self.dtype in ("bf16", "f16") else np.float32
 
     def scaled(self, **kw) -> "WorkloadConfig":
         """A copy with some fields replaced (smaller job counts for CPU tests)."""
@@ -198,17 +198,31 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> IEEE binary16 bit patterns."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of binary16 bit patterns to fp32."""
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
 def to_f64(cfg_or_dtype, x: np.ndarray) -> np.ndarray:
     """Exact widening of a stored tensor to float64."""
     dtype = cfg_or_dtype if isinstance(cfg_or_dtype, str) else cfg_or_dtype.dtype
     if dtype == "bf16":
         return bf16_bits_to_f32(x).astype(np.float64)
+    if dtype == "f16":
+        return f16_bits_to_f32(x).astype(np.float64)
     return np.asarray(x, dtype=np.float32).astype(np.float64)
 
 
 def _normal(cfg: WorkloadConfig, rng: np.random.Generator, shape) -> np.ndarray:
     x = rng.standard_normal(size=shape, dtype=np.float32)
-    return f32_to_bf16_bits(x) if cfg.dtype == "bf16" else x
+    if cfg.dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    return f32_to_f16_bits(x) if cfg.dtype == "f16" else x
 
 
 def job_cache(cfg: WorkloadConfig, seed: int, job: int, length: int):

@@ -48,7 +48,9 @@ typedef struct fs_pool fs_pool; /* opaque; created and destroyed by the library 
 
 typedef enum fs_dtype {
     FS_BF16 = 0, /* 2-byte bfloat16 pool, q, k, v                         */
-    FS_F32 = 1   /* 4-byte IEEE float pool, q, k, v                       */
+    FS_F32 = 1,  /* 4-byte IEEE float pool, q, k, v                       */
+    FS_F16 = 2   /* 2-byte IEEE half pool, q, k, v (the precision of the
+                    paper's runs, Section 6.1)                            */
 } fs_dtype;
 
 typedef enum fs_status {

@@ -21,8 +21,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fs_oracle.c")
 _LIB = os.path.join(_HERE, "libfs_oracle.so")
 
-DTYPE_CODE = {"bf16": 0, "f32": 1, "f64": 2}
-_NP_OF = {"bf16": np.uint16, "f32": np.float32, "f64": np.float64}
+DTYPE_CODE = {"bf16": 0, "f32": 1, "f64": 2, "f16": 3}
+_NP_OF = {"bf16": np.uint16, "f16": np.uint16, "f32": np.float32, "f64": np.float64}
 
 _lib = None
 
@@ -63,7 +63,7 @@ def attention_job(q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: str,
                   length: Optional[int] = None, scale: float = 0.0,
                   heads: Optional[Sequence[int]] = None, want_weights: bool = False):
     """Attention of one job's new token.  q [H][D]; K, V [>=L][H][D] in `dtype`
-    storage (bf16 as uint16 bits).  Returns out [H][D] float64 (rows outside
+    storage (bf16 and f16 as uint16 bits).  Returns out [H][D] float64 (rows outside
     `heads`=(h0,h1) are zero) and, if asked, the weights [H][L]."""
     lib = _load()
     H, D = q.shape

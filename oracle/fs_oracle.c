@@ -21,7 +21,8 @@
  * (Section 2.2, block-grained allocation) is a storage matter and does not
  * exist here: a job's cache is one contiguous logical array K[t][h][d].
  *
- * All arithmetic is IEEE double; bf16 and fp32 inputs widen exactly.
+ * All arithmetic is IEEE double; bf16, fp16 and fp32 inputs widen exactly.
+ * (fp16 is the precision of the paper's own runs, Section 6.1.)
  * Single-threaded, no blocking, no reordering.
  */
 #include <math.h>
@@ -30,11 +31,11 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { FSO_BF16 = 0, FSO_F32 = 1, FSO_F64 = 2 };
+enum { FSO_BF16 = 0, FSO_F32 = 1, FSO_F64 = 2, FSO_F16 = 3 };
 
 static size_t elem_size(int dtype)
 {
-    return dtype == FSO_BF16 ? 2 : dtype == FSO_F32 ? 4 : 8;
+    return (dtype == FSO_BF16 || dtype == FSO_F16) ? 2 : dtype == FSO_F32 ? 4 : 8;
 }
 
 /* exact widening of element i of a typed array */
@@ -45,6 +46,20 @@ static double load_elem(const void *base, int dtype, size_t i)
         float f;
         memcpy(&f, &bits, sizeof f);
         return (double)f;
+    }
+    if (dtype == FSO_F16) {
+        /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        uint16_t h = ((const uint16_t *)base)[i];
+        int e = (h >> 10) & 0x1f;
+        double frac = (double)(h & 0x3ff) / 1024.0;
+        double mag;
+        if (e == 0)
+            mag = ldexp(frac, -14);                 /* zero and subnormals */
+        else if (e == 31)
+            mag = (h & 0x3ff) ? NAN : INFINITY;
+        else
+            mag = ldexp(1.0 + frac, e - 15);
+        return (h & 0x8000) ? -mag : mag;
     }
     if (dtype == FSO_F32)
         return (double)((const float *)base)[i];

@@ -17,7 +17,7 @@ import torch  # first: the library binds to the HIP runtime torch has loaded
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FS_LIBRARY") or os.path.join(_HERE, "libfastserve.so")
 
-FS_BF16, FS_F32 = 0, 1
+FS_BF16, FS_F32, FS_F16 = 0, 1, 2
 FS_OK = 0
 FS_ERR_INVALID_ARG, FS_ERR_OOM, FS_ERR_BAD_TABLE, FS_ERR_HIP, FS_ERR_UNSUPPORTED = -1, -2, -3, -4, -5
 KERNEL_KINDS = ("append", "attention", "combine", "prefill")
@@ -145,11 +145,11 @@ class Pool:
             raise RuntimeError("no GPU visible: the decode path runs on the GPU only")
         lib = load_library()
         self.dtype = dtype
-        self.torch_dtype = {"bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+        self.torch_dtype = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
         self.num_heads, self.head_dim, self.block_size = num_heads, head_dim, block_size
         self.num_blocks, self.num_host_blocks = num_blocks, num_host_blocks
         cfg = fs_pool_config()
-        cfg.dtype = {"bf16": FS_BF16, "f32": FS_F32}[dtype]
+        cfg.dtype = {"bf16": FS_BF16, "f16": FS_F16, "f32": FS_F32}[dtype]
         cfg.num_heads, cfg.head_dim, cfg.block_size = num_heads, head_dim, block_size
         cfg.num_blocks, cfg.num_host_blocks = num_blocks, num_host_blocks
         cfg.max_jobs, cfg.max_workgroups, cfg.scale, cfg.reserved = max_jobs, max_workgroups, scale, 0

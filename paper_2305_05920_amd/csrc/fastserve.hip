@@ -68,8 +68,10 @@ constexpr int kWindowSteps = kWindowBlocks / kStepBlocks;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 struct BF16 { static constexpr int kBytes = 2; };
+struct F16 { static constexpr int kBytes = 2; };
 struct F32 { static constexpr int kBytes = 4; };
 
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
@@ -86,6 +88,15 @@ __device__ __forceinline__ float dot16<BF16>(uint32_t k0, uint32_t k1, uint32_t 
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k1), __builtin_bit_cast(bf16x2, q1), acc, false);
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k2), __builtin_bit_cast(bf16x2, q2), acc, false);
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k3), __builtin_bit_cast(bf16x2, q3), acc, false);
+    return acc;
+}
+template <>
+__device__ __forceinline__ float dot16<F16>(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3,
+                                            uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3, float acc) {
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, k0), __builtin_bit_cast(f16x2, q0), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, k1), __builtin_bit_cast(f16x2, q1), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, k2), __builtin_bit_cast(f16x2, q2), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, k3), __builtin_bit_cast(f16x2, q3), acc, false);
     return acc;
 }
 template <>
@@ -111,6 +122,19 @@ __device__ __forceinline__ void axpy16<BF16>(float p, uint32_t v0, uint32_t v1, 
     acc[5] = fmaf(p, as_f32(v2 & 0xffff0000u), acc[5]);
     acc[6] = fmaf(p, as_f32(v3 << 16), acc[6]);
     acc[7] = fmaf(p, as_f32(v3 & 0xffff0000u), acc[7]);
+}
+template <>
+__device__ __forceinline__ void axpy16<F16>(float p, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, float *acc) {
+    const f16x2 h0 = __builtin_bit_cast(f16x2, v0), h1 = __builtin_bit_cast(f16x2, v1);
+    const f16x2 h2 = __builtin_bit_cast(f16x2, v2), h3 = __builtin_bit_cast(f16x2, v3);
+    acc[0] = fmaf(p, (float)h0.x, acc[0]);
+    acc[1] = fmaf(p, (float)h0.y, acc[1]);
+    acc[2] = fmaf(p, (float)h1.x, acc[2]);
+    acc[3] = fmaf(p, (float)h1.y, acc[3]);
+    acc[4] = fmaf(p, (float)h2.x, acc[4]);
+    acc[5] = fmaf(p, (float)h2.y, acc[5]);
+    acc[6] = fmaf(p, (float)h3.x, acc[6]);
+    acc[7] = fmaf(p, (float)h3.y, acc[7]);
 }
 template <>
 __device__ __forceinline__ void axpy16<F32>(float p, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, float *acc) {
@@ -974,7 +998,7 @@ extern "C" {
 int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
 {
     if (!cfg || !out) return FS_ERR_INVALID_ARG;
-    if (cfg->dtype != FS_BF16 && cfg->dtype != FS_F32) return FS_ERR_UNSUPPORTED;
+    if (cfg->dtype != FS_BF16 && cfg->dtype != FS_F32 && cfg->dtype != FS_F16) return FS_ERR_UNSUPPORTED;
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return FS_ERR_UNSUPPORTED;
     if (cfg->block_size != kBlockTokens) return FS_ERR_UNSUPPORTED;
     if (cfg->num_heads <= 0 || cfg->num_heads > 65535 || cfg->num_blocks <= 0 || cfg->num_host_blocks < 0 ||
@@ -984,7 +1008,7 @@ int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
     fs_pool *p = new (std::nothrow) fs_pool();
     if (!p) return FS_ERR_OOM;
     p->cfg = *cfg;
-    p->elem_bytes = cfg->dtype == FS_BF16 ? 2 : 4;
+    p->elem_bytes = cfg->dtype == FS_F32 ? 4 : 2;
     p->block_bytes = (size_t)2 * cfg->num_heads * kBlockTokens * cfg->head_dim * p->elem_bytes;
     p->scale = cfg->scale > 0.f ? cfg->scale : (float)(1.0 / std::sqrt((double)cfg->head_dim));
     p->max_jobs = cfg->max_jobs > 0 ? cfg->max_jobs : 1024;
@@ -1170,6 +1194,8 @@ static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_ne
            : launch_attention<E, DD, false>(p, qs, ks, vs, ts, stride, ls, n, max_len, os, s))
         if (p->cfg.dtype == FS_BF16)
             rc = D == 128 ? FS_LAUNCH(BF16, 128) : FS_LAUNCH(BF16, 64);
+        else if (p->cfg.dtype == FS_F16)
+            rc = D == 128 ? FS_LAUNCH(F16, 128) : FS_LAUNCH(F16, 64);
         else
             rc = D == 128 ? FS_LAUNCH(F32, 128) : FS_LAUNCH(F32, 64);
 #undef FS_LAUNCH

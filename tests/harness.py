@@ -19,14 +19,15 @@ REL_L2_TOL = 5e-3
 
 
 def to_torch(cfg_dtype: str, a: np.ndarray, device="cuda") -> torch.Tensor:
-    """Host array in storage form (bf16 as uint16 bits) -> device tensor of the pool dtype."""
-    if cfg_dtype == "bf16":
-        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    """Host array in storage form (bf16, f16 as uint16 bits) -> device tensor of the pool dtype."""
+    if cfg_dtype in ("bf16", "f16"):
+        t = torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device)
+        return t.view(torch.bfloat16 if cfg_dtype == "bf16" else torch.float16)
     return torch.from_numpy(np.ascontiguousarray(a)).to(device)
 
 
 def from_torch(cfg_dtype: str, t: torch.Tensor) -> np.ndarray:
-    if cfg_dtype == "bf16":
+    if cfg_dtype in ("bf16", "f16"):
         return t.view(torch.int16).cpu().numpy().view(np.uint16)
     return t.cpu().numpy()
 
@@ -36,7 +37,7 @@ def layout_of(cfg: wl.WorkloadConfig) -> PoolLayout:
 
 
 def sentinel_of(cfg: wl.WorkloadConfig):
-    return np.uint16(0x7FC1) if cfg.dtype == "bf16" else np.float32(-12345.678)
+    return np.uint16(0x7FC1) if cfg.dtype in ("bf16", "f16") else np.float32(-12345.678)
 
 
 @dataclass

@@ -47,6 +47,29 @@ def test_step_matches_oracle_and_layout(idx, rep):
     hs.assert_parity(got, hs.oracle_step(case), f"{cfg.name} rep {rep}")
 
 
+@pytest.mark.parametrize("idx,fused", [(1, False), (1, True), (2, False), (3, True)])
+def test_half_precision_pool_matches_oracle_and_layout(idx, fused):
+    # IEEE half storage, the precision of the paper's own runs (Section 6.1)
+    cfg = wl.CONFIGS[idx].scaled(dtype="f16")
+    print(f"[case] f16 preset {cfg.name} fused={fused}", flush=True)
+    case = hs.make_case(cfg, 0)
+    bt = case.step.tables
+    want_img = hs.expected_image(case, bt.table, bt.num_blocks, upto="prefix")
+    if fused:
+        run = hs.DeviceRun(case, fill="image", prefix_image=want_img)
+        try:
+            got = run.fused_step(max_len_hint=int(case.step.lens.max()))
+            run.pool.check()
+            img = run.image()
+        finally:
+            run.close()
+    else:
+        got, img = run_full_step(case, fill="image", prefix_image=want_img)
+    hs.append_into(want_img, case, bt.table)
+    assert np.array_equal(img.view(np.uint8), want_img.view(np.uint8)), "pool image differs from the layout model"
+    hs.assert_parity(got, hs.oracle_step(case), f"f16 {cfg.name}")
+
+
 @pytest.mark.parametrize("rep", [0, 1, 2])
 def test_long_context_reduced_job_count(rep):
     # preset 4 with 2 of its 8 jobs at a quarter of the length: same heads, same
@@ -134,7 +157,7 @@ def test_fused_step_matches_oracle_and_layout(idx, rep):
     hs.assert_parity(got, hs.oracle_step(case), f"fused {cfg.name} rep {rep}")
 
 
-@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128), ("f16", 128), ("f16", 64)])
 def test_fused_step_boundaries(dtype, D):
     # lengths after the append; 1 means an empty cache before the step, 65 a cache of
     # exactly one full 64-token unit, 17 a new token that opens a new block
@@ -229,7 +252,7 @@ def test_append_copies_any_bit_pattern():
 EDGE_LENS = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1000]
 
 
-@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128), ("f16", 128), ("f16", 64)])
 def test_block_and_step_boundaries(dtype, D):
     cfg = wl.CONFIGS[1].scaled(num_jobs=len(EDGE_LENS), num_heads=5, head_dim=D, dtype=dtype, max_len=1024)
     case = hs.make_case(cfg, 0, lens=EDGE_LENS)

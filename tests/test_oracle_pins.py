@@ -198,19 +198,43 @@ def test_large_scores_do_not_overflow():
 
 
 # ---- storage types widen exactly ------------------------------------------
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 def test_stored_types_widen_exactly(dtype):
     H, D, L = 4, 64, 45
     q, K, V = rand_job(15, L, H, D)
     if dtype == "bf16":
         sq, sK, sV = (f32_to_bf16_bits(a.astype(np.float32)) for a in (q, K, V))
         wq, wK, wV = (bf16_bits_to_f32(a).astype(np.float64) for a in (sq, sK, sV))
+    elif dtype == "f16":
+        sq, sK, sV = (a.astype(np.float16).view(np.uint16) for a in (q, K, V))
+        wq, wK, wV = (a.view(np.float16).astype(np.float64) for a in (sq, sK, sV))
     else:
         sq, sK, sV = (a.astype(np.float32) for a in (q, K, V))
         wq, wK, wV = (a.astype(np.float64) for a in (sq, sK, sV))
     a = oracle.attention_job(sq, sK, sV, dtype)
     b = oracle.attention_job(wq, wK, wV, "f64")
     assert np.array_equal(a, b)
+
+
+def test_every_finite_half_bit_pattern_widens_to_its_ieee_value():
+    # a one-token cache returns its value row (weight exactly 1): all 63488 finite binary16
+    # patterns, subnormals included, against numpy's float16
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    finite = (bits & 0x7C00) != 0x7C00
+    bits = np.where(finite, bits, 0).astype(np.uint16)
+    V = bits.reshape(1, 512, 128)
+    K = np.zeros_like(V)
+    q = np.zeros((512, 128), dtype=np.uint16)
+    out = oracle.attention_job(q, K, V, "f16")
+    want = bits.view(np.float16).astype(np.float64).reshape(512, 128)
+    assert np.array_equal(out, want)
+    nz = want != 0                     # a sum that starts at +0 does not keep the sign of -0
+    assert np.array_equal(np.signbit(out[nz]), np.signbit(want[nz]))
+    # and the known corner values of the format
+    corner = np.array([0x0001, 0x03FF, 0x0400, 0x3C00, 0x7BFF, 0xC000], dtype=np.uint16)
+    Vc = np.zeros((1, 1, 6), dtype=np.uint16); Vc[0, 0] = corner
+    oc = oracle.attention_job(np.zeros((1, 6), np.uint16), np.zeros_like(Vc), Vc, "f16")
+    assert oc[0].tolist() == [2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14, 1.0, 65504.0, -2.0]
 
 
 def test_bf16_rounding_helper_is_round_to_nearest_even():
