@@ -13,7 +13,7 @@ from __future__ import annotations
 import ctypes
 import os
 import subprocess
-from typing import Optional, Sequence
+from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -48,6 +48,8 @@ def _load():
         lib.fso_attention_job.restype = i32
         lib.fso_decode_step.argtypes = [vp, vp, vp, i32, i32, i32, i32, dbl, vp, vp, vp, vp]
         lib.fso_decode_step.restype = i32
+        lib.fso_prefill_attention_job.argtypes = [vp, vp, vp, i32, lng, i32, i32, dbl, i32, i32, vp]
+        lib.fso_prefill_attention_job.restype = i32
         _lib = lib
     return _lib
 
@@ -82,6 +84,26 @@ def attention_job(q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: str,
     if rc:
         raise RuntimeError(f"fso_attention_job failed: {rc}")
     return (out, w[:, :L]) if want_weights else out
+
+
+def prefill_attention_job(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dtype: str,
+                          scale: Optional[float] = None, heads: Optional[Tuple[int, int]] = None) -> np.ndarray:
+    """Initialization-phase attention of one job's prompt.  Q, K, V [s][H][D] in `dtype`
+    storage; returns out [s][H][D] float64 (heads outside `heads` stay zero): token i
+    attends to tokens 0..i."""
+    lib = _load()
+    _check(Q, dtype, "Q"), _check(K, dtype, "K"), _check(V, dtype, "V")
+    if Q.shape != K.shape or Q.shape != V.shape or Q.ndim != 3:
+        raise ValueError("Q, K, V must share the shape [s][H][D]")
+    s, H, D = Q.shape
+    h0, h1 = heads if heads is not None else (0, H)
+    out = np.zeros((s, H, D), dtype=np.float64)
+    rc = lib.fso_prefill_attention_job(Q.ctypes.data if s else None, K.ctypes.data if s else None,
+                                       V.ctypes.data if s else None, DTYPE_CODE[dtype], s, H, D,
+                                       -1.0 if scale is None else float(scale), h0, h1, out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fso_prefill_attention_job failed ({rc})")
+    return out
 
 
 class LogicalCaches:

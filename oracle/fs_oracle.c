@@ -160,3 +160,61 @@ int fso_decode_step(void *const *K, void *const *V, const long *lens_before,
     }
     return 0;
 }
+
+/*
+ * Initialization phase (paper Section 2.2, Figure 3, first iteration): all s
+ * prompt tokens of a job are processed at once; token i's masked self-attention
+ * sees the keys and values of tokens 0..i of the same prompt and nothing later.
+ * Written out:
+ *
+ *     s_it       = scale * sum_d Q[i][h][d] * K[t][h][d]        0 <= t <= i
+ *     w_it       = exp(s_it - max_{u<=i} s_iu) / sum_{u<=i} exp(s_iu - max ...)
+ *     out[i][h]  = sum_{t<=i} w_it * V[t][h][:]
+ *
+ *   Q, K, V: [s][H][D]   out: [s][H][D] doubles, heads [h0, h1) written.
+ */
+int fso_prefill_attention_job(const void *Q, const void *K, const void *V, int dtype,
+                              long s, int H, int D, double scale, int h0, int h1,
+                              double *out)
+{
+    if (s < 0 || H <= 0 || D <= 0 || h0 < 0 || h1 > H || h0 > h1)
+        return -1;
+    if (s == 0)
+        return 0;
+    if (!Q || !K || !V || !out)
+        return -1;
+    if (scale <= 0.0)
+        scale = 1.0 / sqrt((double)D);
+    double *sc = (double *)malloc(sizeof(double) * (size_t)s);
+    if (!sc)
+        return -2;
+    for (long i = 0; i < s; ++i) {
+        for (int h = h0; h < h1; ++h) {
+            double *o = out + ((size_t)i * H + h) * D;
+            double smax = -INFINITY;
+            for (long t = 0; t <= i; ++t) {
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d)
+                    dot += load_elem(Q, dtype, ((size_t)i * H + h) * D + d) *
+                           load_elem(K, dtype, ((size_t)t * H + h) * D + d);
+                sc[t] = scale * dot;
+                if (sc[t] > smax)
+                    smax = sc[t];
+            }
+            double denom = 0.0;
+            for (long t = 0; t <= i; ++t) {
+                sc[t] = exp(sc[t] - smax);
+                denom += sc[t];
+            }
+            for (int d = 0; d < D; ++d)
+                o[d] = 0.0;
+            for (long t = 0; t <= i; ++t) {
+                double w = sc[t] / denom;
+                for (int d = 0; d < D; ++d)
+                    o[d] += w * load_elem(V, dtype, ((size_t)t * H + h) * D + d);
+            }
+        }
+    }
+    free(sc);
+    return 0;
+}
