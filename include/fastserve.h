@@ -135,6 +135,31 @@ int fs_kv_prefill(fs_pool *pool, const int32_t *block_table, int32_t table_strid
                   const int32_t *job_starts, const int32_t *token_offsets, int32_t num_jobs,
                   int64_t total_tokens, const void *k, const void *v, void *stream);
 
+/* ---- prompt attention (Section 2.2 and Figure 3, initialization phase: the first
+ *      iteration of a job processes all its input tokens; masked self-attention lets
+ *      token i see tokens 0..i of its own prompt) -----------------------------------
+ * For every job j and every token i of its prompt:
+ *     out[t0+i][h][:] = sum_{t<=i} softmax_t(scale * q[t0+i][h] . k[t0+t][h]) * v[t0+t][h][:]
+ * with t0 = token_offsets[j].  The keys and values are read from the packed projection
+ * arrays (the same ones fs_kv_prefill writes into the pool), not from the pool; the pool
+ * handle supplies dtype, H, D and scale.  Runs on the matrix cores with fp32
+ * accumulation; the softmax weights are rounded to the pool dtype before they multiply
+ * the values.
+ *   q, k, v:       device [total_tokens][H][D], pool dtype (FS_BF16 or FS_F16;
+ *                  FS_F32 pools return FS_ERR_UNSUPPORTED)
+ *   token_offsets: device int32 [num_jobs+1], non-decreasing, [0] = 0,
+ *                  [num_jobs] = total_tokens
+ *   total_tokens:  the same total, known to the host
+ *   max_tokens:    host-side upper bound of the longest prompt (sizes the launch);
+ *                  <= 0 means total_tokens.  A prompt longer than the bound, or offsets
+ *                  that leave [0, total_tokens], raise the pool's error flag
+ *                  (fs_pool_check) and such rows are not written.
+ *   out:           device float32 [total_tokens][H][D]; every row is written.
+ * Asynchronous on `stream`; nothing is allocated. */
+int fs_prefill_attention(fs_pool *pool, const void *q, const void *k, const void *v,
+                         const int32_t *token_offsets, int32_t num_jobs, int64_t total_tokens,
+                         int32_t max_tokens, float *out, void *stream);
+
 /* ---- decode attention (Section 2.2: masked self-attention of the one new token
  *      over the keys and values of all tokens up to and including itself) ------------
  * For every job j and head h, with L = job_lens[j] (tokens to attend over, i.e.
@@ -186,8 +211,9 @@ typedef enum fs_kernel_kind {
     FS_KERNEL_APPEND = 0,
     FS_KERNEL_ATTENTION = 1, /* partitioned attention with online softmax             */
     FS_KERNEL_COMBINE = 2,   /* merge of the partitions of one (job, head)            */
-    FS_KERNEL_PREFILL = 3,
-    FS_KERNEL_KINDS = 4
+    FS_KERNEL_PREFILL = 3,           /* bulk KV write                                  */
+    FS_KERNEL_PREFILL_ATTENTION = 4, /* prompt-phase attention                         */
+    FS_KERNEL_KINDS = 5
 } fs_kernel_kind;
 
 /* While enabled, every kernel launch carries a pair of HIP events on its stream that the

@@ -793,6 +793,8 @@ __global__ __launch_bounds__(kThreads) void fs_kv_prefill_kernel(
     *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
 }
 
+#include "prefill_attention.hpp"
+
 // ------------------------------------------------------------------------------------
 // Plain streaming kernels of known size: the practical HBM ceiling on this GPU and the
 // scale factor of the hardware byte counters.  Not part of the decode path.
@@ -1161,6 +1163,36 @@ int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_
         launch_kernel(p, FS_KERNEL_PREFILL, fs_kv_prefill_kernel<4>, dim3((unsigned)wgs), s, p->mem, table, stride,
                       starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, (const char *)k,
                       (const char *)v, p->err);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+int fs_prefill_attention(fs_pool *p, const void *q, const void *k, const void *v, const int32_t *offs, int32_t J,
+                         int64_t total_tokens, int32_t max_tokens, float *out, void *stream)
+{
+    if (!p || J < 0 || total_tokens < 0) return FS_ERR_INVALID_ARG;
+    if (J == 0 || total_tokens == 0) return FS_OK;
+    if (!q || !k || !v || !offs || !out) return FS_ERR_INVALID_ARG;
+    if (total_tokens > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    if (p->cfg.dtype == FS_F32) return FS_ERR_UNSUPPORTED;  // the matrix-core path takes 2-byte operands
+    if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
+    const int H = p->cfg.num_heads, D = p->cfg.head_dim;
+    long long longest = max_tokens > 0 && max_tokens < total_tokens ? max_tokens : total_tokens;
+    const long long qtiles = (longest + kPfQTile - 1) / kPfQTile;
+    const long long pairs_padded = ((long long)J * H + kXcds - 1) / kXcds * kXcds;
+    if (qtiles * pairs_padded > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 grid((unsigned)(qtiles * pairs_padded));
+    const float c = p->scale * 1.4426950408889634f;
+#define FS_PF_LAUNCH(E, DD)                                                                                   \
+    launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD>, grid, s, (const char *)q,     \
+                  (const char *)k, (const char *)v, offs, out, J, H, (int32_t)pairs_padded, (int32_t)qtiles,   \
+                  (long long)total_tokens, c, p->err)
+    if (p->cfg.dtype == FS_BF16) {
+        if (D == 128) FS_PF_LAUNCH(BF16, 128); else FS_PF_LAUNCH(BF16, 64);
+    } else {
+        if (D == 128) FS_PF_LAUNCH(F16, 128); else FS_PF_LAUNCH(F16, 64);
+    }
+#undef FS_PF_LAUNCH
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 

@@ -1,0 +1,128 @@
+"""GPU parity of the prompt-phase attention (matrix-core kernel, called through the C ABI)
+against the CPU oracle's causal definition, prompt by prompt."""
+import numpy as np
+import pytest
+import torch
+
+import fs_workload as wl
+import oracle
+from tests import harness as hs
+
+pytestmark = pytest.mark.gpu
+
+
+def make_prompts(dtype, lens, H, D, seed):
+    rng = np.random.default_rng(seed)
+    T = int(sum(lens))
+    conv = wl.f32_to_bf16_bits if dtype == "bf16" else wl.f32_to_f16_bits
+    q, k, v = (conv(rng.standard_normal((T, H, D), dtype=np.float32)) for _ in range(3))
+    offs = np.zeros(len(lens) + 1, dtype=np.int32)
+    offs[1:] = np.cumsum(lens)
+    return q, k, v, offs
+
+
+def run_device(dtype, H, D, q, k, v, offs, max_tokens=None, guard=3):
+    import paper_2305_05920_amd as fs
+    T = q.shape[0]
+    pool = fs.Pool(dtype, H, D, 4)
+    try:
+        # rows past T must stay untouched; rows inside must all be written
+        out = torch.full((T + guard, H, D), float("nan"), dtype=torch.float32, device="cuda")
+        lens = np.diff(offs)
+        mt = int(lens.max(initial=0)) if max_tokens is None else max_tokens
+        fs.fs_prefill_attention(pool, hs.to_torch(dtype, q), hs.to_torch(dtype, k), hs.to_torch(dtype, v),
+                                torch.from_numpy(offs).cuda(), out[:T], max_tokens=mt)
+        torch.cuda.synchronize()
+        pool.check()
+        got = out.cpu().numpy()
+    finally:
+        pool.close()
+    assert np.isnan(got[T:]).all(), "rows past the last token were written"
+    return got[:T]
+
+
+def oracle_prompts(dtype, q, k, v, offs):
+    ref = np.zeros(q.shape, dtype=np.float64)
+    for j in range(len(offs) - 1):
+        a, b = int(offs[j]), int(offs[j + 1])
+        if b > a:
+            ref[a:b] = oracle.prefill_attention_job(np.ascontiguousarray(q[a:b]), np.ascontiguousarray(k[a:b]),
+                                                    np.ascontiguousarray(v[a:b]), dtype)
+    return ref
+
+
+EDGE_LENS = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 257, 0, 5]
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("f16", 128), ("f16", 64)])
+def test_tile_boundaries_and_ragged_prompts(dtype, D):
+    print(f"[case] prefill attention edges {dtype} D={D}", flush=True)
+    H = 3
+    q, k, v, offs = make_prompts(dtype, EDGE_LENS, H, D, 11)
+    got = run_device(dtype, H, D, q, k, v, offs)
+    assert np.isfinite(got).all()
+    ref = oracle_prompts(dtype, q, k, v, offs)
+    hs.assert_parity(got, ref, f"prefill attention edges {dtype} D={D}")
+    # the first token of every prompt returns its own value row (its only weight is 1 up to
+    # the rounding of the fused scale-and-subtract in front of the exponential)
+    for j, n in enumerate(EDGE_LENS):
+        if n:
+            np.testing.assert_allclose(got[offs[j]].astype(np.float64), wl.to_f64(dtype, v[offs[j]]), rtol=5e-7, atol=0)
+
+
+@pytest.mark.parametrize("rep", [0, 1])
+def test_prompt_lengths_of_the_headline_preset(rep):
+    # prompt lengths drawn as the cache lengths of preset 1 (exponential, mean 512), fewer heads
+    cfg = wl.CONFIGS[1].scaled(num_jobs=6, num_heads=4)
+    lens = wl.job_lens(cfg, wl.seed_for(cfg.index, rep)).tolist()
+    print(f"[case] prefill attention preset-1 lengths {lens}", flush=True)
+    q, k, v, offs = make_prompts("bf16", lens, cfg.num_heads, cfg.head_dim, 77 + rep)
+    got = run_device("bf16", cfg.num_heads, cfg.head_dim, q, k, v, offs)
+    hs.assert_parity(got, oracle_prompts("bf16", q, k, v, offs), f"prefill attention preset 1 rep {rep}")
+
+
+def test_long_prompt_spans_many_key_tiles():
+    lens = [1500, 700]
+    q, k, v, offs = make_prompts("bf16", lens, 2, 128, 5)
+    got = run_device("bf16", 2, 128, q, k, v, offs)
+    hs.assert_parity(got, oracle_prompts("bf16", q, k, v, offs), "prefill attention long")
+
+
+def test_default_launch_bound_and_zero_jobs():
+    import paper_2305_05920_amd as fs
+    q, k, v, offs = make_prompts("bf16", [70, 9], 2, 64, 6)
+    got = run_device("bf16", 2, 64, q, k, v, offs, max_tokens=0)      # bound = total tokens
+    hs.assert_parity(got, oracle_prompts("bf16", q, k, v, offs), "prefill attention default bound")
+    pool = fs.Pool("bf16", 2, 64, 4)
+    e = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device="cuda")
+    fs.fs_prefill_attention(pool, e, e, e, torch.zeros(1, dtype=torch.int32, device="cuda"),
+                            torch.zeros((0, 2, 64), dtype=torch.float32, device="cuda"))
+    pool.check()
+    pool.close()
+
+
+def test_bad_offsets_and_short_bound_raise_the_flag():
+    import paper_2305_05920_amd as fs
+    H, D = 2, 64
+    q, k, v, offs = make_prompts("bf16", [40, 300], H, D, 7)
+    for bad_offs, mt in ((np.array([0, 40, 999], np.int32), 300),        # runs past the arrays
+                         (np.array([0, 60, 40], np.int32), 300),          # decreasing
+                         (offs, 128)):                                    # a prompt longer than the bound
+        pool = fs.Pool("bf16", H, D, 4)
+        out = torch.zeros((340, H, D), dtype=torch.float32, device="cuda")
+        fs.fs_prefill_attention(pool, hs.to_torch("bf16", q), hs.to_torch("bf16", k), hs.to_torch("bf16", v),
+                                torch.from_numpy(bad_offs).cuda(), out, max_tokens=mt)
+        torch.cuda.synchronize()
+        with pytest.raises(fs.FsError):
+            pool.check()
+        pool.close()
+
+
+def test_float_pools_are_refused():
+    import paper_2305_05920_amd as fs
+    pool = fs.Pool("f32", 2, 64, 4)
+    x = torch.zeros((8, 2, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(fs.FsError) as ei:
+        fs.fs_prefill_attention(pool, x, x, x, torch.tensor([0, 8], dtype=torch.int32, device="cuda"), x.clone())
+    assert ei.value.status == fs.FS_ERR_UNSUPPORTED
+    pool.close()
