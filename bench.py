@@ -240,6 +240,73 @@ def cpu_baseline(reps, budget_s=12.0):
             "seconds_per_step": best}, out
 
 
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix-core peak
+
+
+def prefill_phase(fs, torch, wl, cfg, reps, log):
+    """Initialization phase on the preset's shape: the jobs' lengths taken as prompt lengths,
+    packed q, k, v [T][H][D]; fs_kv_prefill writes the cache blocks, fs_prefill_attention
+    computes the causal attention of every prompt token.  Kernel times from launch-attached
+    events; flops = 4*D per (query, visible key) pair and head."""
+    if cfg.dtype == "f32":
+        return None
+    lens = wl.job_lens(cfg, wl.seed_for(cfg.index, 0)).astype(np.int64)
+    H, D = cfg.num_heads, cfg.head_dim
+    T = int(lens.sum())
+    offs = np.zeros(cfg.num_jobs + 1, dtype=np.int32)
+    offs[1:] = np.cumsum(lens)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(wl.seed_for(cfg.index, 0))
+    q, k, v = (torch.randn((T, H, D), generator=g, device="cuda", dtype=torch.float32).to(tdt) for _ in range(3))
+    out = torch.empty((T, H, D), dtype=torch.float32, device="cuda")
+    nblk = (lens + cfg.block_size - 1) // cfg.block_size
+    W = int(nblk.max())
+    table = np.full((cfg.num_jobs, W), -1, dtype=np.int32)
+    nb = 0
+    for j in range(cfg.num_jobs):
+        table[j, :nblk[j]] = np.arange(nb, nb + nblk[j])
+        nb += int(nblk[j])
+    pool = fs.Pool(cfg.dtype, H, D, nb)
+    try:
+        d_table, d_offs = torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda()
+        d_starts = torch.zeros(cfg.num_jobs, dtype=torch.int32, device="cuda")
+        mt = int(lens.max())
+
+        def once():
+            fs.fs_kv_prefill(pool, d_table, d_starts, d_offs, T, k, v)
+            fs.fs_prefill_attention(pool, q, k, v, d_offs, out, max_tokens=mt)
+
+        for _ in range(3):
+            once()
+        torch.cuda.synchronize()
+        pool.profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            once()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / reps
+        prof = pool.profile_collect()
+        pool.profile_enable(False)
+        pool.check()
+        attn_ms = prof["prefill_attention"]["ms"] / max(prof["prefill_attention"]["launches"], 1)
+        write_ms = prof["prefill"]["ms"] / max(prof["prefill"]["launches"], 1)
+        flops = float(4 * D * H * (lens * (lens + 1) // 2).sum())
+        hbm_bytes = float(T * H * D * (3 * cfg.elem_bytes + 4))
+        res = {"workload": f"{cfg.name} lengths as prompts: {cfg.num_jobs} prompts, {T} tokens, {H} heads x {D}, {cfg.dtype}",
+               "ms_per_pass": wall_ms, "prompt_tokens_per_s": T / (wall_ms / 1e3),
+               "kernel_ms": {"prefill_attention": attn_ms, "kv_write": write_ms},
+               "roofline": {"bound": "mfma", "achieved": flops / (attn_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
+                            "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                            "traffic": None, "kernel": "fs_prefill_attn_kernel", "flops_per_launch": flops,
+                            "alg_bytes_per_launch": hbm_bytes,
+                            "alg_gbps": hbm_bytes / (attn_ms * 1e-3) / 1e9}}
+        log(json.dumps(res))
+        return res
+    finally:
+        pool.close()
+
+
 def load_traffic(cfg_name):
     """HBM bytes per attention launch measured with rocprofv3 --pmc (committed summary)."""
     path = os.path.join(ROOT, "profiles", f"attn_partition_{cfg_name}_traffic.txt")
@@ -269,6 +336,8 @@ def main():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the initialization-phase measurement")
+    ap.add_argument("--only-prefill", action="store_true", help="measure the initialization phase alone")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the plain stream read/copy kernels over 1 GiB (scale of hardware byte counters)")
     args = ap.parse_args()
@@ -341,6 +410,10 @@ def main():
         finally:
             reps.close()
 
+    if args.only_prefill:
+        cfg = wl.CONFIGS[args.config] if not args.dtype else wl.CONFIGS[args.config].scaled(dtype=args.dtype)
+        print(json.dumps(prefill_phase(fs, torch, wl, cfg, 20, log)), flush=True)
+        return
     main_res, base = measure(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
     others = []
     for tok in [t for t in args.also.split(",") if t.strip()]:
@@ -383,6 +456,8 @@ def main():
         "rel_l2_err": main_res.get("rel_l2_err"),
         "other_workloads": others,
     }
+    if not args.no_prefill:
+        line["prefill_phase"] = prefill_phase(fs, torch, wl, cfg, 20, log)
     print(json.dumps(line), flush=True)
 
 

@@ -8,17 +8,21 @@
 //
 // Work split.  A workgroup of 4 waves owns 128 consecutive query rows of one (job, head);
 // wave w owns rows [32w, 32w+32) of them.  Keys and values of the pair are walked in
-// tiles of 64 tokens, staged once per workgroup in LDS: keys as they lie in memory
-// ([key][d], rows padded by 16 B), values transposed ([d][key], rows padded by 16 B), so
-// that both matrix-core operands are plain 16-byte (keys) or 8-byte (values) LDS reads.
+// tiles of 64 tokens, staged once per workgroup in LDS as they lie in memory ([token][d],
+// rows padded against bank conflicts).  The key operand is a plain 16-byte LDS read; the
+// value operand needs 4 consecutive tokens of one head-dim index per lane, which is what
+// the LDS transpose read of gfx950 (ds_read_b64_tr_b16) returns: in a group of 16 lanes,
+// lane L receives the 2-byte element L % 4 of the 8 bytes that lanes 4e + L/4 (e = 0..3)
+// point at, i.e. column L of a 4 x 16 block whose rows those lanes address.
 //
 // Per tile a wave computes the transposed score tile S^T = K Q^T (keys x query rows): in
 // the accumulator layout of the 32x32 instruction a lane then holds 16 keys of ONE query
 // row (row = lane % 32, the other 16 keys sit in lane ^ 32), so the softmax statistics
 // are per-lane scalars and need one exchange between the two half-waves.  The same
 // registers, rounded to the storage type, are exactly the B operand of O^T = V^T P^T for
-// the key order k = 8*(e/4) + 4*(lane/32) + e%4, which the reads of V^T follow; no
-// cross-lane movement of the probabilities is needed.
+// the key order k = 8*(e/4) + 4*(lane/32) + e%4, which the reads of V follow; no
+// cross-lane movement of the probabilities is needed.  At the end a wave passes its output
+// tile through LDS so that every global store covers whole 256-byte pieces of a row.
 #pragma once
 
 constexpr int kPfQTile = 128;  // query rows per workgroup
@@ -31,6 +35,7 @@ typedef _Float16 pf_f16x2 __attribute__((ext_vector_type(2)));
 typedef float pf_f32x16 __attribute__((ext_vector_type(16)));
 typedef float pf_f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t pf_u32x2 __attribute__((ext_vector_type(2)));
+typedef short pf_i16x4 __attribute__((ext_vector_type(4)));
 
 template <typename E>
 struct PfMath;
@@ -58,30 +63,37 @@ struct PfMath<F16> {
 };
 
 // q, k, v: [total_tokens][H][D] (2-byte elements), jobs packed back to back; offs[J+1].
-// out: [total_tokens][H][D] fp32.  Grid: num_qtiles * pairs_padded workgroups; workgroup b
-// serves pair b % pairs_padded (pairs_padded is a multiple of 8, so all tiles of a pair
-// land on the same die and share its L2) and query tile num_qtiles-1 - b/pairs_padded
-// (the tiles with the most keys start first).
+// out: [total_tokens][H][D] fp32.  Grid: num_qtiles * pairs_padded workgroups (pairs_padded a
+// multiple of 8).  Workgroup b runs on die b % 8 as that die's (b / 8)-th workgroup; the die
+// walks its pairs (pair % 8 == die) one after the other and, inside a pair, the query tiles
+// from the last (most keys) to the first.  The tiles of a pair so run at the same time on
+// one die and find the pair's keys and values in that die's L2.
 template <typename E, int D>
 __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     const char *__restrict__ q, const char *__restrict__ k, const char *__restrict__ v,
     const int32_t *__restrict__ offs, float *__restrict__ out, int32_t J, int32_t H, int32_t pairs_padded,
     int32_t num_qtiles, long long total_tokens, float scale_log2e, int32_t *__restrict__ err)
 {
-    constexpr int kKStride = D * 2 + 16;         // bytes per staged key row
-    constexpr int kVStride = kPfKTile * 2 + 16;  // bytes per staged row of V^T
-    constexpr int NC = D / 16;                   // 16-wide chunks of the head dimension
-    constexpr int ND = D / 32;                   // 32-wide tiles of the output's head dimension
-    constexpr int kKChunks = D / 8;              // 16-byte chunks per key row
-    constexpr int kKRowsPerPass = kThreads / kKChunks;
-    constexpr int KP = kPfKTile / kKRowsPerPass;  // key-staging passes
-    constexpr int VP = kKChunks / 8;              // value-staging passes (8 chunks per pass)
-    __shared__ __attribute__((aligned(16))) char ks[kPfKTile * kKStride];
-    __shared__ __attribute__((aligned(16))) char vt[D * kVStride];
+    constexpr int kKStride = D * 2 + 16;  // bytes per staged key row: 16 rows hit 16 different bank groups
+    constexpr int kVStride = D * 2 + 32;  // bytes per staged value row: 4 rows of a transpose read do
+    constexpr int NC = D / 16;            // 16-wide chunks of the head dimension
+    constexpr int ND = D / 32;            // 32-wide tiles of the output's head dimension
+    constexpr int kChunks = D / 8;        // 16-byte chunks per token row
+    constexpr int kRowsPerPass = kThreads / kChunks;
+    constexpr int SP = kPfKTile / kRowsPerPass;  // staging passes per tile
+    constexpr int kKBytes = kPfKTile * kKStride;
+    constexpr int kVBytes = kPfKTile * kVStride;
+    constexpr int kOutCols = D / 2;                   // output columns a wave stages per pass
+    constexpr int kOutStride = kOutCols * 4 + 16;     // bytes per staged output row
+    static_assert(kWavesPerWg * 32 * kOutStride <= kKBytes + kVBytes, "output staging must fit the tile buffers");
+    __shared__ __attribute__((aligned(16))) char lds[kKBytes + kVBytes];
+    char *const ks = lds;
+    char *const vs = lds + kKBytes;
 
     const int b = blockIdx.x;
-    const int pair = b % pairs_padded;
-    const int qt = num_qtiles - 1 - b / pairs_padded;
+    const int seq = b / kXcds;
+    const int pair = (seq / num_qtiles) * kXcds + b % kXcds;
+    const int qt = num_qtiles - 1 - seq % num_qtiles;
     if (pair >= J * H) return;
     const int j = pair / H, h = pair - j * H;
     const long long t0 = offs[j], t1 = offs[j + 1];
@@ -116,44 +128,38 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     const int last_row = (qt * kPfQTile + kPfQTile < s ? qt * kPfQTile + kPfQTile : s) - 1;
     const int nkt = last_row / kPfKTile + 1;
 
-    // staging roles of this thread
-    const int k_row = threadIdx.x / kKChunks, k_chunk = threadIdx.x % kKChunks;
-    const int v_pair = threadIdx.x & 31, v_chunk = threadIdx.x >> 5;  // keys 2*v_pair, 2*v_pair+1
-    u32x4 kr[KP], vr[VP][2];
+    // staging role of this thread: 16 bytes of token row st_row (+ kRowsPerPass per pass)
+    const int st_row = threadIdx.x / kChunks, st_chunk = threadIdx.x % kChunks;
+    u32x4 kr[SP], vr[SP];
 
     auto load_tile = [&](int kt) {
-        const int key0 = kt * kPfKTile;
 #pragma unroll
-        for (int p = 0; p < KP; ++p) {
-            int row = key0 + k_row + p * kKRowsPerPass;
+        for (int p = 0; p < SP; ++p) {
+            int row = kt * kPfKTile + st_row + p * kRowsPerPass;
             row = row < s ? row : s - 1;
-            kr[p] = *(const u32x4 *)(kb + (size_t)row * tok_bytes + k_chunk * 16);
+            kr[p] = *(const u32x4 *)(kb + (size_t)row * tok_bytes + st_chunk * 16);
+            vr[p] = *(const u32x4 *)(vb + (size_t)row * tok_bytes + st_chunk * 16);
         }
-#pragma unroll
-        for (int p = 0; p < VP; ++p)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                int row = key0 + 2 * v_pair + u;
-                row = row < s ? row : s - 1;
-                vr[p][u] = *(const u32x4 *)(vb + (size_t)row * tok_bytes + (v_chunk + 8 * p) * 16);
-            }
     };
     auto store_tile = [&]() {
 #pragma unroll
-        for (int p = 0; p < KP; ++p)
-            *(u32x4 *)(ks + (k_row + p * kKRowsPerPass) * kKStride + k_chunk * 16) = kr[p];
-#pragma unroll
-        for (int p = 0; p < VP; ++p) {
-            const u32x4 x = vr[p][0], y = vr[p][1];
-            const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
-            char *dst = vt + ((v_chunk + 8 * p) * 8) * kVStride + v_pair * 4;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                // element 2w of both keys, then element 2w+1 of both keys
-                *(uint32_t *)(dst + (2 * w) * kVStride) = (xs[w] & 0xffffu) | (ys[w] << 16);
-                *(uint32_t *)(dst + (2 * w + 1) * kVStride) = (xs[w] >> 16) | (ys[w] & 0xffff0000u);
-            }
+        for (int p = 0; p < SP; ++p) {
+            *(u32x4 *)(ks + (st_row + p * kRowsPerPass) * kKStride + st_chunk * 16) = kr[p];
+            *(u32x4 *)(vs + (st_row + p * kRowsPerPass) * kVStride + st_chunk * 16) = vr[p];
         }
+    };
+
+    // A operand number i of O^T += V^T P^T: head-dim rows 32*(i%ND) + r, keys 16*(i/ND) +
+    // {4hh..4hh+3, 8+4hh..8+4hh+3} of the staged tile.  In its group of 16 lanes this lane
+    // addresses token 4hh + (lane%16)/4 and the 4 head-dim indices 16*((lane/16)%2) + 4*(lane%4) ..
+    const char *const vlane = vs + (4 * hh + ((lane & 15) >> 2)) * kVStride + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    auto v_operand = [&](int i) {
+        typedef pf_i16x4 __attribute__((address_space(3))) * lds_i16x4_ptr;
+        const char *p0 = vlane + (16 * (i / ND)) * kVStride + (i % ND) * 64;
+        const pf_i16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)p0);
+        const pf_i16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p0 + 8 * kVStride));
+        const pf_u32x2 w0 = __builtin_bit_cast(pf_u32x2, a0), w1 = __builtin_bit_cast(pf_u32x2, a1);
+        return u32x4{w0.x, w0.y, w1.x, w1.y};
     };
 
     pf_f32x16 o[ND];
@@ -171,17 +177,33 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
         __syncthreads();
         if (kt + 1 < nkt) load_tile(kt + 1);  // in flight while this tile is computed
         const int key0 = kt * kPfKTile;
-        if (key0 > row0 + 31) continue;  // wave-uniform: the whole tile lies in this wave's future
+        // wave-uniform: the whole tile lies in this wave's future, or the wave has no row of the prompt
+        if (key0 > row0 + 31 || row0 >= s) continue;
 
-        // S^T = K Q^T for the two 32-key halves of the tile
+        // S^T = K Q^T for the two 32-key halves of the tile.  The LDS reads run ahead of the
+        // matrix instructions that use them: the operands of a half are in flight while the
+        // previous half multiplies, and the first value operands while the second half does.
         pf_f32x16 sc[2];
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
+        for (int e = 0; e < 16; ++e) sc[0][e] = 0.f, sc[1][e] = 0.f;
+        u32x4 a[NC];
+        {
+            const char *krow = ks + r * kKStride + hh * 16;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sc[kh][e] = 0.f;
-            const char *krow = ks + (kh * 32 + r) * kKStride + hh * 16;
+            for (int c = 0; c < NC; ++c) a[c] = *(const u32x4 *)(krow + c * 32);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int c = 0; c < NC; ++c) sc[kh] = PfMath<E>::mfma(*(const u32x4 *)(krow + c * 32), qf[c], sc[kh]);
+            for (int c = 0; c < NC; ++c) {
+                sc[0] = PfMath<E>::mfma(a[c], qf[c], sc[0]);
+                a[c] = *(const u32x4 *)(krow + 32 * kKStride + c * 32);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                sc[1] = PfMath<E>::mfma(a[c], qf[c], sc[1]);
+                a[c] = v_operand(c);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (key0 + kPfKTile - 1 > row0) {  // wave-uniform: the tile crosses the diagonal
 #pragma unroll
@@ -218,31 +240,48 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
         }
-        // O^T += V^T P^T
+        // O^T += V^T P^T: operand i covers keys 16*(i/ND).. of the tile and output rows
+        // 32*(i%ND)..; the first NC operands are already in registers
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kc = 0; kc < 4; ++kc) {
+        for (int i = 0; i < 4 * ND; ++i) {
+            const int kc = i / ND;
             const u32x4 pv = u32x4{pb[kc][0], pb[kc][1], pb[kc][2], pb[kc][3]};
-#pragma unroll
-            for (int t = 0; t < ND; ++t) {
-                const char *vrow = vt + (t * 32 + r) * kVStride + (kc * 16 + 4 * hh) * 2;
-                const pf_u32x2 a0 = *(const pf_u32x2 *)vrow;
-                const pf_u32x2 a1 = *(const pf_u32x2 *)(vrow + 16);
-                o[t] = PfMath<E>::mfma(u32x4{a0.x, a0.y, a1.x, a1.y}, pv, o[t]);
-            }
+            o[i % ND] = PfMath<E>::mfma(a[i % NC], pv, o[i % ND]);
+            if (i + NC < 4 * ND) a[i % NC] = v_operand(i + NC);
+            __builtin_amdgcn_sched_barrier(0);  // keep each refill right behind the instruction that frees its registers
         }
     }
 
     // the denominators of the two half-waves belong to the same rows
     l += __shfl_xor(l, 32, 64);
-    if (qrow < s) {
-        const float inv = 1.f / l;
-        float *ob = out + ((size_t)t0 + qrow) * ((size_t)H * D) + (size_t)h * D;
+    const float inv = 1.f / l;
+    // Output: the wave's 32 x D tile goes through LDS in two passes of D/2 columns, so that a
+    // row's columns leave in one piece (16 lanes x 16 bytes) instead of 16 bytes per lane.
+    __syncthreads();  // the tile buffers are free
+    char *const stage = lds + wave * (32 * kOutStride);
+    constexpr int kLanesPerRow = kOutCols / 4;        // lanes that cover a staged row with 16 bytes each
+    constexpr int kRowsPerStore = 64 / kLanesPerRow;  // rows one store instruction covers
+    const int out_row = lane / kLanesPerRow, out_col = (lane % kLanesPerRow) * 4;
+    float *const ob = out + ((size_t)t0 + row0) * ((size_t)H * D) + (size_t)h * D;
 #pragma unroll
-        for (int t = 0; t < ND; ++t)
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+        for (int tt = 0; tt < ND / 2; ++tt) {
+            const int t = pass * (ND / 2) + tt;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 pf_f32x4 w = {o[t][4 * i] * inv, o[t][4 * i + 1] * inv, o[t][4 * i + 2] * inv, o[t][4 * i + 3] * inv};
-                *(pf_f32x4 *)(ob + t * 32 + 8 * i + 4 * hh) = w;
+                *(pf_f32x4 *)(stage + r * kOutStride + (tt * 32 + 8 * i + 4 * hh) * 4) = w;
             }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int it = 0; it < 32 / kRowsPerStore; ++it) {
+            const int row = it * kRowsPerStore + out_row;
+            const pf_f32x4 w = *(const pf_f32x4 *)(stage + row * kOutStride + out_col * 4);
+            if (row0 + row < s) *(pf_f32x4 *)(ob + (size_t)row * ((size_t)H * D) + pass * kOutCols + out_col) = w;
+        }
+        wave_lds_sync();
     }
 }
