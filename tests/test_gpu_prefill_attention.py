@@ -118,6 +118,33 @@ def test_bad_offsets_and_short_bound_raise_the_flag():
         pool.close()
 
 
+def test_a_bad_job_leaves_the_valid_ones_served():
+    import paper_2305_05920_amd as fs
+    H, D = 2, 64
+    q, k, v, offs = make_prompts("bf16", [40, 300], H, D, 7)
+    ref = oracle_prompts("bf16", q, k, v, offs)
+    pool = fs.Pool("bf16", H, D, 4)
+    out = torch.full((340, H, D), float("nan"), dtype=torch.float32, device="cuda")
+    fs.fs_prefill_attention(pool, hs.to_torch("bf16", q), hs.to_torch("bf16", k), hs.to_torch("bf16", v),
+                            torch.tensor([0, 40, 999], dtype=torch.int32, device="cuda"), out, max_tokens=300)
+    torch.cuda.synchronize()
+    with pytest.raises(fs.FsError):
+        pool.check()
+    pool.close()
+    got = out.cpu().numpy()
+    hs.assert_parity(got[:40], ref[:40], "valid job beside a bad one")
+    assert np.isnan(got[40:]).all(), "rows of the bad job were written"
+
+
+def test_many_short_prompts():
+    # 1100 prompts of 1..5 tokens: far more (job, head) pairs than tiles of work
+    rng = np.random.default_rng(3)
+    lens = rng.integers(1, 6, size=1100).tolist()
+    q, k, v, offs = make_prompts("bf16", lens, 2, 64, 8)
+    got = run_device("bf16", 2, 64, q, k, v, offs)
+    hs.assert_parity(got, oracle_prompts("bf16", q, k, v, offs), "prefill attention 1100 short prompts")
+
+
 def test_float_pools_are_refused():
     import paper_2305_05920_amd as fs
     pool = fs.Pool("f32", 2, 64, 4)
