@@ -271,11 +271,10 @@ def prefill_phase(fs, torch, wl, cfg, reps, log):
     try:
         d_table, d_offs = torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda()
         d_starts = torch.zeros(cfg.num_jobs, dtype=torch.int32, device="cuda")
-        mt = int(lens.max())
 
         def once():
             fs.fs_kv_prefill(pool, d_table, d_starts, d_offs, T, k, v)
-            fs.fs_prefill_attention(pool, q, k, v, d_offs, out, max_tokens=mt)
+            fs.fs_prefill_attention(pool, q, k, v, d_offs, out)
 
         for _ in range(3):
             once()
@@ -295,7 +294,8 @@ def prefill_phase(fs, torch, wl, cfg, reps, log):
         hbm_bytes = float(T * H * D * (3 * cfg.elem_bytes + 4))
         res = {"workload": f"{cfg.name} lengths as prompts: {cfg.num_jobs} prompts, {T} tokens, {H} heads x {D}, {cfg.dtype}",
                "ms_per_pass": wall_ms, "prompt_tokens_per_s": T / (wall_ms / 1e3),
-               "kernel_ms": {"prefill_attention": attn_ms, "kv_write": write_ms},
+               "kernel_ms": {"prefill_attention": attn_ms, "kv_write": write_ms,
+                             "work_list": prof["prefill_plan"]["ms"] / max(prof["prefill_plan"]["launches"], 1)},
                "roofline": {"bound": "mfma", "achieved": flops / (attn_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
                             "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                             "traffic": None, "kernel": "fs_prefill_attn_kernel", "flops_per_launch": flops,

@@ -149,16 +149,19 @@ int fs_kv_prefill(fs_pool *pool, const int32_t *block_table, int32_t table_strid
  *                  FS_F32 pools return FS_ERR_UNSUPPORTED)
  *   token_offsets: device int32 [num_jobs+1], non-decreasing, [0] = 0,
  *                  [num_jobs] = total_tokens
- *   total_tokens:  the same total, known to the host
- *   max_tokens:    host-side upper bound of the longest prompt (sizes the launch);
- *                  <= 0 means total_tokens.  A prompt longer than the bound, or offsets
- *                  that leave [0, total_tokens], raise the pool's error flag
- *                  (fs_pool_check) and such rows are not written.
- *   out:           device float32 [total_tokens][H][D]; every row is written.
- * Asynchronous on `stream`; nothing is allocated. */
+ *   total_tokens:  the same total, known to the host.  A job whose offsets decrease or
+ *                  leave [0, total_tokens] raises the pool's error flag (fs_pool_check)
+ *                  and its rows are not written; so does a launch with more than 262144
+ *                  work items (128 query rows x 8 heads each), which is served in part.
+ *   out:           device float32 [total_tokens][H][D]; every row of a valid job is
+ *                  written.
+ * A one-workgroup kernel first derives the work list from the offsets on the device
+ * (longest jobs and largest query tiles first); the host needs no prompt length.
+ * Asynchronous on `stream`; nothing is allocated; calls on one pool share the list and
+ * must be ordered by the stream. */
 int fs_prefill_attention(fs_pool *pool, const void *q, const void *k, const void *v,
                          const int32_t *token_offsets, int32_t num_jobs, int64_t total_tokens,
-                         int32_t max_tokens, float *out, void *stream);
+                         float *out, void *stream);
 
 /* ---- decode attention (Section 2.2: masked self-attention of the one new token
  *      over the keys and values of all tokens up to and including itself) ------------
@@ -213,7 +216,8 @@ typedef enum fs_kernel_kind {
     FS_KERNEL_COMBINE = 2,   /* merge of the partitions of one (job, head)            */
     FS_KERNEL_PREFILL = 3,           /* bulk KV write                                  */
     FS_KERNEL_PREFILL_ATTENTION = 4, /* prompt-phase attention                         */
-    FS_KERNEL_KINDS = 5
+    FS_KERNEL_PREFILL_PLAN = 5,      /* its work list                                  */
+    FS_KERNEL_KINDS = 6
 } fs_kernel_kind;
 
 /* While enabled, every kernel launch carries a pair of HIP events on its stream that the

@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("FS_LIBRARY") or os.path.join(_HERE, "libfastserve.so"
 FS_BF16, FS_F32, FS_F16 = 0, 1, 2
 FS_OK = 0
 FS_ERR_INVALID_ARG, FS_ERR_OOM, FS_ERR_BAD_TABLE, FS_ERR_HIP, FS_ERR_UNSUPPORTED = -1, -2, -3, -4, -5
-KERNEL_KINDS = ("append", "attention", "combine", "prefill", "prefill_attention")
+KERNEL_KINDS = ("append", "attention", "combine", "prefill", "prefill_attention", "prefill_plan")
 
 EXPORTS = (
     "fs_pool_create", "fs_pool_destroy", "fs_pool_block_bytes", "fs_pool_device_ptr",
@@ -74,7 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_pool_check.argtypes = [vp, vp]
     lib.fs_kv_append.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
     lib.fs_kv_prefill.argtypes = [vp, vp, i32, vp, vp, i32, i64, vp, vp, vp]
-    lib.fs_prefill_attention.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, vp, vp]
+    lib.fs_prefill_attention.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, vp]
     lib.fs_decode_attention.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
     lib.fs_decode_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, vp, vp]
     lib.fs_pool_offload.argtypes = [vp, vp, vp, i32, vp]
@@ -272,8 +272,7 @@ def fs_kv_prefill(pool: Pool, block_table: torch.Tensor, job_starts: torch.Tenso
 
 
 def fs_prefill_attention(pool: Pool, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
-                         token_offsets: torch.Tensor, out: torch.Tensor, max_tokens: int = 0,
-                         stream=None) -> None:
+                         token_offsets: torch.Tensor, out: torch.Tensor, stream=None) -> None:
     """Prompt-phase attention over packed prompts q, k, v [T][H][D]: token i of a job attends
     to tokens 0..i of the same job; out [T][H][D] float32."""
     J = token_offsets.numel() - 1
@@ -285,7 +284,7 @@ def fs_prefill_attention(pool: Pool, q: torch.Tensor, k: torch.Tensor, v: torch.
     _ok(pool._lib.fs_prefill_attention(pool._h, _dev(q, "q", pool.torch_dtype), _dev(k, "k", pool.torch_dtype),
                                        _dev(v, "v", pool.torch_dtype),
                                        _dev(token_offsets, "token_offsets", torch.int32), J, int(T),
-                                       int(max_tokens), _dev(out, "out", torch.float32), _stream_ptr(stream)),
+                                       _dev(out, "out", torch.float32), _stream_ptr(stream)),
         "fs_prefill_attention")
 
 

@@ -897,6 +897,7 @@ struct fs_pool {
     float *part_acc = nullptr;
     float *part_ml = nullptr;
     int32_t *plan = nullptr;
+    PfItem *pf_items = nullptr;  // work list of the prompt-attention launches: count, then entries
     int32_t *err = nullptr;
 #ifdef FS_TRACE
     unsigned long long *trace = nullptr;
@@ -1046,6 +1047,9 @@ int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
     if (rc == FS_OK) rc = alloc_scratch(p);
     if (rc == FS_OK && hipMalloc((void **)&p->plan, (kMaxJobsPerLaunch + 2) * sizeof(int32_t)) != hipSuccess)
         rc = FS_ERR_OOM;
+    if (rc == FS_OK && p->elem_bytes == 2 &&
+        hipMalloc((void **)&p->pf_items, (size_t)(kPfMaxItems + 1) * sizeof(PfItem)) != hipSuccess)
+        rc = FS_ERR_OOM;
     if (rc == FS_OK && hipMalloc((void **)&p->err, 256) != hipSuccess) rc = FS_ERR_OOM;
     if (rc == FS_OK && (hipMemset(p->err, 0, 256) != hipSuccess ||
                         hipMemset(p->plan, 0, (kMaxJobsPerLaunch + 2) * sizeof(int32_t)) != hipSuccess))
@@ -1076,6 +1080,7 @@ int fs_pool_destroy(fs_pool *p)
     if (p->part_acc) (void)hipFree(p->part_acc);
     if (p->part_ml) (void)hipFree(p->part_ml);
     if (p->plan) (void)hipFree(p->plan);
+    if (p->pf_items) (void)hipFree(p->pf_items);
     if (p->err) (void)hipFree(p->err);
     delete p;
     return FS_OK;
@@ -1167,7 +1172,7 @@ int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_
 }
 
 int fs_prefill_attention(fs_pool *p, const void *q, const void *k, const void *v, const int32_t *offs, int32_t J,
-                         int64_t total_tokens, int32_t max_tokens, float *out, void *stream)
+                         int64_t total_tokens, float *out, void *stream)
 {
     if (!p || J < 0 || total_tokens < 0) return FS_ERR_INVALID_ARG;
     if (J == 0 || total_tokens == 0) return FS_OK;
@@ -1176,23 +1181,27 @@ int fs_prefill_attention(fs_pool *p, const void *q, const void *k, const void *v
     if (p->cfg.dtype == FS_F32) return FS_ERR_UNSUPPORTED;  // the matrix-core path takes 2-byte operands
     if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
     const int H = p->cfg.num_heads, D = p->cfg.head_dim;
-    long long longest = max_tokens > 0 && max_tokens < total_tokens ? max_tokens : total_tokens;
-    const long long qtiles = (longest + kPfQTile - 1) / kPfQTile;
-    const long long pairs_padded = ((long long)J * H + kXcds - 1) / kXcds * kXcds;
-    if (qtiles * pairs_padded > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
+    const int G = (H + kXcds - 1) / kXcds;  // head groups: one head per die and group
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid((unsigned)(qtiles * pairs_padded));
     const float c = p->scale * 1.4426950408889634f;
-#define FS_PF_LAUNCH(E, DD)                                                                                   \
-    launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD>, grid, s, (const char *)q,     \
-                  (const char *)k, (const char *)v, offs, out, J, H, (int32_t)pairs_padded, (int32_t)qtiles,   \
-                  (long long)total_tokens, c, p->err)
-    if (p->cfg.dtype == FS_BF16) {
-        if (D == 128) FS_PF_LAUNCH(BF16, 128); else FS_PF_LAUNCH(BF16, 64);
-    } else {
-        if (D == 128) FS_PF_LAUNCH(F16, 128); else FS_PF_LAUNCH(F16, 64);
-    }
+    for (int j0 = 0; j0 < J; j0 += kMaxJobsPerLaunch) {
+        const int n = (J - j0) < kMaxJobsPerLaunch ? (J - j0) : kMaxJobsPerLaunch;
+        launch_kernel(p, FS_KERNEL_PREFILL_PLAN, fs_prefill_plan_kernel, dim3(1), s, offs + j0, n, G,
+                      (long long)total_tokens, p->pf_items, p->err);
+        // the list cannot be longer than one entry per started 128 tokens of every job and head group
+        long long entries = ((long long)total_tokens / kPfQTile + n) * G;
+        if (entries > kPfMaxItems) entries = kPfMaxItems;
+        const dim3 grid((unsigned)(entries * kXcds));
+#define FS_PF_LAUNCH(E, DD)                                                                                 \
+    launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD>, grid, s, (const char *)q,   \
+                  (const char *)k, (const char *)v, (const PfItem *)p->pf_items, out, H, c)
+        if (p->cfg.dtype == FS_BF16) {
+            if (D == 128) FS_PF_LAUNCH(BF16, 128); else FS_PF_LAUNCH(BF16, 64);
+        } else {
+            if (D == 128) FS_PF_LAUNCH(F16, 128); else FS_PF_LAUNCH(F16, 64);
+        }
 #undef FS_PF_LAUNCH
+    }
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 

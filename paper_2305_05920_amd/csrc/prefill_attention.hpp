@@ -63,16 +63,93 @@ struct PfMath<F16> {
 };
 
 // q, k, v: [total_tokens][H][D] (2-byte elements), jobs packed back to back; offs[J+1].
-// out: [total_tokens][H][D] fp32.  Grid: num_qtiles * pairs_padded workgroups (pairs_padded a
-// multiple of 8).  Workgroup b runs on die b % 8 as that die's (b / 8)-th workgroup; the die
-// walks its pairs (pair % 8 == die) one after the other and, inside a pair, the query tiles
-// from the last (most keys) to the first.  The tiles of a pair so run at the same time on
-// one die and find the pair's keys and values in that die's L2.
+// out: [total_tokens][H][D] fp32.  `items` is the work list fs_prefill_plan_kernel wrote: entry
+// seq names a job (its first token and length), a group of 8 heads and a query tile.
+// Workgroup b runs on die b % 8 as that die's (b / 8)-th workgroup and serves entry b / 8 with
+// head 8 * group + b % 8.  The list walks the jobs from the longest down and, inside a
+// (job, head group), the query tiles from the last (most keys) to the first: the tiles of a
+// (job, head) so run at the same time on one die and find its keys and values in that
+// die's L2, and the long items start first.
+// One work-list entry: 128 query rows of 8 heads' worth of workgroups.
+struct PfItem {
+    int32_t t0;     // first token of the job in the packed arrays
+    int32_t s;      // prompt length
+    int32_t qt;     // query tile
+    int32_t group;  // head group: heads 8*group .. 8*group+7
+};
+constexpr int kPfMaxItems = 262144;  // entries the pool's work list holds
+
+// Builds the work list of a launch (one workgroup).  offs[J+1], J <= 1024; G head groups.
+// items[0].t0 receives the entry count, entries follow from items[1].  A job whose offsets
+// decrease or leave [0, total_tokens] raises the flag and gets no entry.
+__global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t *__restrict__ offs, int32_t J,
+                                                                   int32_t G, long long total_tokens,
+                                                                   PfItem *__restrict__ items,
+                                                                   int32_t *__restrict__ err)
+{
+    __shared__ int32_t s_len[kMaxJobsPerLaunch];
+    __shared__ int32_t s_t0[kMaxJobsPerLaunch];
+    __shared__ uint16_t s_ord[kMaxJobsPerLaunch];   // job by rank, longest prompt first
+    __shared__ int32_t s_base[kMaxJobsPerLaunch + 1];  // first entry of the job of that rank
+    bool bad = false;
+    for (int j = threadIdx.x; j < J; j += kThreads) {
+        const long long a = offs[j], b = offs[j + 1];
+        const bool ok = a >= 0 && b >= a && b <= total_tokens;
+        bad |= !ok;
+        s_len[j] = ok ? (int32_t)(b - a) : 0;
+        s_t0[j] = (int32_t)a;
+    }
+    if (bad) atomicOr(err, kErrBadLen);
+    __syncthreads();
+    for (int j = threadIdx.x; j < J; j += kThreads) {
+        const int mine = s_len[j];
+        int rank = 0;
+        for (int i = 0; i < J; ++i) {
+            const int li = s_len[i];
+            rank += (li > mine || (li == mine && i < j)) ? 1 : 0;
+        }
+        s_ord[rank] = (uint16_t)j;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long acc = 0;
+        for (int rk = 0; rk < J; ++rk) {
+            s_base[rk] = (int32_t)acc;
+            acc += (long long)((s_len[s_ord[rk]] + kPfQTile - 1) / kPfQTile) * G;
+            if (acc > kPfMaxItems) {  // more work than the list holds: serve what fits, say so
+                atomicOr(err, kErrBadLen);
+                acc = s_base[rk];
+                for (int r2 = rk; r2 <= J; ++r2) s_base[r2] = (int32_t)acc;
+                break;
+            }
+        }
+        s_base[J] = (int32_t)acc;
+        items[0].t0 = (int32_t)acc;
+    }
+    __syncthreads();
+    const int total = s_base[J];
+    for (int e = threadIdx.x; e < total; e += kThreads) {
+        int lo = 0, hi = J;  // largest rank with s_base[rank] <= e (ranks without entries share a base)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_base[mid] <= e) lo = mid; else hi = mid;
+        }
+        const int j = s_ord[lo];
+        const int tiles = (s_len[j] + kPfQTile - 1) / kPfQTile;
+        const int rem = e - s_base[lo];
+        PfItem it;
+        it.t0 = s_t0[j];
+        it.s = s_len[j];
+        it.group = rem / tiles;
+        it.qt = tiles - 1 - rem % tiles;
+        items[1 + e] = it;
+    }
+}
+
 template <typename E, int D>
 __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     const char *__restrict__ q, const char *__restrict__ k, const char *__restrict__ v,
-    const int32_t *__restrict__ offs, float *__restrict__ out, int32_t J, int32_t H, int32_t pairs_padded,
-    int32_t num_qtiles, long long total_tokens, float scale_log2e, int32_t *__restrict__ err)
+    const PfItem *__restrict__ items, float *__restrict__ out, int32_t H, float scale_log2e)
 {
     constexpr int kKStride = D * 2 + 16;  // bytes per staged key row: 16 rows hit 16 different bank groups
     constexpr int kVStride = D * 2 + 32;  // bytes per staged value row: 4 rows of a transpose read do
@@ -90,23 +167,13 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     char *const ks = lds;
     char *const vs = lds + kKBytes;
 
-    const int b = blockIdx.x;
-    const int seq = b / kXcds;
-    const int pair = (seq / num_qtiles) * kXcds + b % kXcds;
-    const int qt = num_qtiles - 1 - seq % num_qtiles;
-    if (pair >= J * H) return;
-    const int j = pair / H, h = pair - j * H;
-    const long long t0 = offs[j], t1 = offs[j + 1];
-    if (t0 < 0 || t1 < t0 || t1 > total_tokens) {
-        if (threadIdx.x == 0 && h == 0 && qt == 0) atomicOr(err, kErrBadLen);
-        return;
-    }
-    const int s = (int)(t1 - t0);
-    if (s > num_qtiles * kPfQTile) {  // longer than the launch was sized for
-        if (threadIdx.x == 0 && h == 0 && qt == 0) atomicOr(err, kErrBadLen);
-        return;
-    }
-    if (qt * kPfQTile >= s) return;
+    const int seq = blockIdx.x / kXcds;
+    if (seq >= items[0].t0) return;
+    const PfItem item = items[1 + seq];
+    const int h = item.group * kXcds + blockIdx.x % kXcds;
+    if (h >= H) return;
+    const long long t0 = item.t0;
+    const int s = item.s, qt = item.qt;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, hh = lane >> 5;

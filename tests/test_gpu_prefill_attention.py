@@ -21,17 +21,15 @@ def make_prompts(dtype, lens, H, D, seed):
     return q, k, v, offs
 
 
-def run_device(dtype, H, D, q, k, v, offs, max_tokens=None, guard=3):
+def run_device(dtype, H, D, q, k, v, offs, guard=3):
     import paper_2305_05920_amd as fs
     T = q.shape[0]
     pool = fs.Pool(dtype, H, D, 4)
     try:
         # rows past T must stay untouched; rows inside must all be written
         out = torch.full((T + guard, H, D), float("nan"), dtype=torch.float32, device="cuda")
-        lens = np.diff(offs)
-        mt = int(lens.max(initial=0)) if max_tokens is None else max_tokens
         fs.fs_prefill_attention(pool, hs.to_torch(dtype, q), hs.to_torch(dtype, k), hs.to_torch(dtype, v),
-                                torch.from_numpy(offs).cuda(), out[:T], max_tokens=mt)
+                                torch.from_numpy(offs).cuda(), out[:T])
         torch.cuda.synchronize()
         pool.check()
         got = out.cpu().numpy()
@@ -88,12 +86,16 @@ def test_long_prompt_spans_many_key_tiles():
     hs.assert_parity(got, oracle_prompts("bf16", q, k, v, offs), "prefill attention long")
 
 
-def test_default_launch_bound_and_zero_jobs():
+def test_zero_jobs_and_all_prompts_empty():
     import paper_2305_05920_amd as fs
-    q, k, v, offs = make_prompts("bf16", [70, 9], 2, 64, 6)
-    got = run_device("bf16", 2, 64, q, k, v, offs, max_tokens=0)      # bound = total tokens
-    hs.assert_parity(got, oracle_prompts("bf16", q, k, v, offs), "prefill attention default bound")
     pool = fs.Pool("bf16", 2, 64, 4)
+    x = torch.zeros((5, 2, 64), dtype=torch.bfloat16, device="cuda")
+    o = torch.full((5, 2, 64), 7.0, dtype=torch.float32, device="cuda")
+    # three jobs without a token: nothing to do, nothing written
+    fs.fs_prefill_attention(pool, x, x, x, torch.zeros(4, dtype=torch.int32, device="cuda"), o)
+    torch.cuda.synchronize()
+    pool.check()
+    assert (o == 7.0).all()
     e = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device="cuda")
     fs.fs_prefill_attention(pool, e, e, e, torch.zeros(1, dtype=torch.int32, device="cuda"),
                             torch.zeros((0, 2, 64), dtype=torch.float32, device="cuda"))
@@ -101,17 +103,16 @@ def test_default_launch_bound_and_zero_jobs():
     pool.close()
 
 
-def test_bad_offsets_and_short_bound_raise_the_flag():
+def test_bad_offsets_raise_the_flag():
     import paper_2305_05920_amd as fs
     H, D = 2, 64
     q, k, v, offs = make_prompts("bf16", [40, 300], H, D, 7)
-    for bad_offs, mt in ((np.array([0, 40, 999], np.int32), 300),        # runs past the arrays
-                         (np.array([0, 60, 40], np.int32), 300),          # decreasing
-                         (offs, 128)):                                    # a prompt longer than the bound
+    for bad_offs in (np.array([0, 40, 999], np.int32),        # job 1 runs past the arrays
+                     np.array([0, 60, 40], np.int32)):        # job 1 decreasing
         pool = fs.Pool("bf16", H, D, 4)
         out = torch.zeros((340, H, D), dtype=torch.float32, device="cuda")
         fs.fs_prefill_attention(pool, hs.to_torch("bf16", q), hs.to_torch("bf16", k), hs.to_torch("bf16", v),
-                                torch.from_numpy(bad_offs).cuda(), out, max_tokens=mt)
+                                torch.from_numpy(bad_offs).cuda(), out)
         torch.cuda.synchronize()
         with pytest.raises(fs.FsError):
             pool.check()
@@ -126,7 +127,7 @@ def test_a_bad_job_leaves_the_valid_ones_served():
     pool = fs.Pool("bf16", H, D, 4)
     out = torch.full((340, H, D), float("nan"), dtype=torch.float32, device="cuda")
     fs.fs_prefill_attention(pool, hs.to_torch("bf16", q), hs.to_torch("bf16", k), hs.to_torch("bf16", v),
-                            torch.tensor([0, 40, 999], dtype=torch.int32, device="cuda"), out, max_tokens=300)
+                            torch.tensor([0, 40, 999], dtype=torch.int32, device="cuda"), out)
     torch.cuda.synchronize()
     with pytest.raises(fs.FsError):
         pool.check()
@@ -136,8 +137,8 @@ def test_a_bad_job_leaves_the_valid_ones_served():
     assert np.isnan(got[40:]).all(), "rows of the bad job were written"
 
 
-def test_many_short_prompts():
-    # 1100 prompts of 1..5 tokens: far more (job, head) pairs than tiles of work
+def test_more_jobs_than_one_launch_slice():
+    # 1100 prompts of 1..5 tokens: two launches (1024 jobs each at most)
     rng = np.random.default_rng(3)
     lens = rng.integers(1, 6, size=1100).tolist()
     q, k, v, offs = make_prompts("bf16", lens, 2, 64, 8)
