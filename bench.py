@@ -272,30 +272,39 @@ def prefill_phase(fs, torch, wl, cfg, reps, log):
         d_table, d_offs = torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda()
         d_starts = torch.zeros(cfg.num_jobs, dtype=torch.int32, device="cuda")
 
-        def once():
+        def two_calls():
             fs.fs_kv_prefill(pool, d_table, d_starts, d_offs, T, k, v)
             fs.fs_prefill_attention(pool, q, k, v, d_offs, out)
 
-        for _ in range(3):
-            once()
-        torch.cuda.synchronize()
-        pool.profile_enable(True)
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            once()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3 / reps
-        prof = pool.profile_collect()
-        pool.profile_enable(False)
-        pool.check()
-        attn_ms = prof["prefill_attention"]["ms"] / max(prof["prefill_attention"]["launches"], 1)
-        write_ms = prof["prefill"]["ms"] / max(prof["prefill"]["launches"], 1)
+        def fused():
+            fs.fs_prefill_step(pool, d_table, d_offs, k, v, q, out)
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            pool.profile_enable(True)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t0) * 1e3 / reps
+            prof = pool.profile_collect()
+            pool.profile_enable(False)
+            pool.check()
+            return wall_ms, {kind: rec["ms"] / max(rec["launches"], 1) for kind, rec in prof.items() if rec["launches"]}
+
+        wall_ms, kms = timed(two_calls)
+        wall_f, kms_f = timed(fused)
+        attn_ms = kms["prefill_attention"]
         flops = float(4 * D * H * (lens * (lens + 1) // 2).sum())
         hbm_bytes = float(T * H * D * (3 * cfg.elem_bytes + 4))
         res = {"workload": f"{cfg.name} lengths as prompts: {cfg.num_jobs} prompts, {T} tokens, {H} heads x {D}, {cfg.dtype}",
                "ms_per_pass": wall_ms, "prompt_tokens_per_s": T / (wall_ms / 1e3),
-               "kernel_ms": {"prefill_attention": attn_ms, "kv_write": write_ms,
-                             "work_list": prof["prefill_plan"]["ms"] / max(prof["prefill_plan"]["launches"], 1)},
+               "kernel_ms": {"prefill_attention": attn_ms, "kv_write": kms["prefill"], "work_list": kms["prefill_plan"]},
+               "fused_step": {"ms_per_pass": wall_f, "prompt_tokens_per_s": T / (wall_f / 1e3),
+                              "kernel_ms": {"prefill_attention": kms_f["prefill_attention"],
+                                            "work_list": kms_f["prefill_plan"]}},
                "roofline": {"bound": "mfma", "achieved": flops / (attn_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
                             "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                             "traffic": None, "kernel": "fs_prefill_attn_kernel", "flops_per_launch": flops,

@@ -163,6 +163,19 @@ int fs_prefill_attention(fs_pool *pool, const void *q, const void *k, const void
                          const int32_t *token_offsets, int32_t num_jobs, int64_t total_tokens,
                          float *out, void *stream);
 
+/* ---- whole initialization phase of a batch of new jobs in one launch (Section 2.2:
+ *      the first iteration builds the cache of all prompt tokens and computes their
+ *      attention; Sections 5-6 on fusing operations into fewer kernels) ---------------
+ * fs_prefill_attention plus the cache fill of fs_kv_prefill with job_starts = 0: token t
+ * of job j is also written to slot t % block_size of block block_table[j][t / block_size]
+ * (bit copy), by the workgroup that has the token's key/value tile staged.  Arguments as
+ * in those two calls; a table entry outside [0, num_blocks) or a prompt longer than
+ * table_stride blocks raises the error flag and that write is skipped.
+ * Jobs must own disjoint blocks. */
+int fs_prefill_step(fs_pool *pool, const int32_t *block_table, int32_t table_stride,
+                    const int32_t *token_offsets, int32_t num_jobs, int64_t total_tokens,
+                    const void *k, const void *v, const void *q, float *out, void *stream);
+
 /* ---- decode attention (Section 2.2: masked self-attention of the one new token
  *      over the keys and values of all tokens up to and including itself) ------------
  * For every job j and head h, with L = job_lens[j] (tokens to attend over, i.e.

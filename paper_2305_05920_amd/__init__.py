@@ -25,7 +25,7 @@ KERNEL_KINDS = ("append", "attention", "combine", "prefill", "prefill_attention"
 EXPORTS = (
     "fs_pool_create", "fs_pool_destroy", "fs_pool_block_bytes", "fs_pool_device_ptr",
     "fs_pool_write_block", "fs_pool_read_block", "fs_pool_check", "fs_kv_append", "fs_kv_prefill",
-    "fs_prefill_attention",
+    "fs_prefill_attention", "fs_prefill_step",
     "fs_decode_attention", "fs_decode_step", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
     "fs_profile_collect", "fs_pool_set_param", "fs_pool_get_param", "fs_pool_last_plan",
     "fs_stream_read", "fs_stream_copy", "fs_strerror", "fs_version",
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_kv_append.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
     lib.fs_kv_prefill.argtypes = [vp, vp, i32, vp, vp, i32, i64, vp, vp, vp]
     lib.fs_prefill_attention.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, vp]
+    lib.fs_prefill_step.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, vp, vp, vp]
     lib.fs_decode_attention.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
     lib.fs_decode_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, vp, vp]
     lib.fs_pool_offload.argtypes = [vp, vp, vp, i32, vp]
@@ -286,6 +287,24 @@ def fs_prefill_attention(pool: Pool, q: torch.Tensor, k: torch.Tensor, v: torch.
                                        _dev(token_offsets, "token_offsets", torch.int32), J, int(T),
                                        _dev(out, "out", torch.float32), _stream_ptr(stream)),
         "fs_prefill_attention")
+
+
+def fs_prefill_step(pool: Pool, block_table: torch.Tensor, token_offsets: torch.Tensor, k: torch.Tensor,
+                    v: torch.Tensor, q: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """The whole initialization phase of new jobs: their prompt tokens' k, v [T][H][D] fill the
+    jobs' cache blocks from position 0 and out [T][H][D] receives the prompt attention."""
+    J = token_offsets.numel() - 1
+    T = q.shape[0]
+    shape = (T, pool.num_heads, pool.head_dim)
+    if J < 0 or block_table.dim() != 2 or block_table.shape[0] != J:
+        raise ValueError("block_table: need [num_jobs][table_stride]; token_offsets [num_jobs+1]")
+    if tuple(q.shape) != shape or tuple(k.shape) != shape or tuple(v.shape) != shape or tuple(out.shape) != shape:
+        raise ValueError(f"q, k, v, out: need shape {shape}")
+    _ok(pool._lib.fs_prefill_step(pool._h, _dev(block_table, "block_table", torch.int32), block_table.shape[1],
+                                  _dev(token_offsets, "token_offsets", torch.int32), J, int(T),
+                                  _dev(k, "k", pool.torch_dtype), _dev(v, "v", pool.torch_dtype),
+                                  _dev(q, "q", pool.torch_dtype), _dev(out, "out", torch.float32),
+                                  _stream_ptr(stream)), "fs_prefill_step")
 
 
 def fs_decode_attention(q: torch.Tensor, pool: Pool, block_table: torch.Tensor, job_lens: torch.Tensor,

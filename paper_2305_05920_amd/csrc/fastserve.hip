@@ -1171,12 +1171,14 @@ int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
-int fs_prefill_attention(fs_pool *p, const void *q, const void *k, const void *v, const int32_t *offs, int32_t J,
-                         int64_t total_tokens, float *out, void *stream)
+static int run_prefill_attention(fs_pool *p, bool write, const int32_t *table, int32_t stride, const void *q,
+                                 const void *k, const void *v, const int32_t *offs, int32_t J, int64_t total_tokens,
+                                 float *out, void *stream)
 {
     if (!p || J < 0 || total_tokens < 0) return FS_ERR_INVALID_ARG;
     if (J == 0 || total_tokens == 0) return FS_OK;
     if (!q || !k || !v || !offs || !out) return FS_ERR_INVALID_ARG;
+    if (write && (!table || stride <= 0)) return FS_ERR_INVALID_ARG;
     if (total_tokens > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
     if (p->cfg.dtype == FS_F32) return FS_ERR_UNSUPPORTED;  // the matrix-core path takes 2-byte operands
     if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
@@ -1192,17 +1194,36 @@ int fs_prefill_attention(fs_pool *p, const void *q, const void *k, const void *v
         long long entries = ((long long)total_tokens / kPfQTile + n) * G;
         if (entries > kPfMaxItems) entries = kPfMaxItems;
         const dim3 grid((unsigned)(entries * kXcds));
-#define FS_PF_LAUNCH(E, DD)                                                                                 \
-    launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD>, grid, s, (const char *)q,   \
-                  (const char *)k, (const char *)v, (const PfItem *)p->pf_items, out, H, c)
-        if (p->cfg.dtype == FS_BF16) {
-            if (D == 128) FS_PF_LAUNCH(BF16, 128); else FS_PF_LAUNCH(BF16, 64);
-        } else {
-            if (D == 128) FS_PF_LAUNCH(F16, 128); else FS_PF_LAUNCH(F16, 64);
-        }
+        const int32_t *ts = write ? table + (size_t)j0 * stride : nullptr;
+#define FS_PF_LAUNCH(E, DD, W)                                                                                 \
+    launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD, W>, grid, s, (const char *)q,   \
+                  (const char *)k, (const char *)v, (const PfItem *)p->pf_items, out, H, c, p->mem, ts, stride, \
+                  p->cfg.num_blocks, p->err)
+#define FS_PF_DISPATCH(W)                                                          \
+    do {                                                                           \
+        if (p->cfg.dtype == FS_BF16) {                                             \
+            if (D == 128) FS_PF_LAUNCH(BF16, 128, W); else FS_PF_LAUNCH(BF16, 64, W); \
+        } else {                                                                   \
+            if (D == 128) FS_PF_LAUNCH(F16, 128, W); else FS_PF_LAUNCH(F16, 64, W);   \
+        }                                                                          \
+    } while (0)
+        if (write) FS_PF_DISPATCH(true); else FS_PF_DISPATCH(false);
+#undef FS_PF_DISPATCH
 #undef FS_PF_LAUNCH
     }
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+int fs_prefill_attention(fs_pool *p, const void *q, const void *k, const void *v, const int32_t *offs, int32_t J,
+                         int64_t total_tokens, float *out, void *stream)
+{
+    return run_prefill_attention(p, false, nullptr, 0, q, k, v, offs, J, total_tokens, out, stream);
+}
+
+int fs_prefill_step(fs_pool *p, const int32_t *table, int32_t stride, const int32_t *offs, int32_t J,
+                    int64_t total_tokens, const void *k, const void *v, const void *q, float *out, void *stream)
+{
+    return run_prefill_attention(p, true, table, stride, q, k, v, offs, J, total_tokens, out, stream);
 }
 
 static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_new, const void *v_new,

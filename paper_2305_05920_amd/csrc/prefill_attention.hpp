@@ -72,14 +72,15 @@ struct PfMath<F16> {
 // die's L2, and the long items start first.
 // One work-list entry: 128 query rows of 8 heads' worth of workgroups.
 struct PfItem {
-    int32_t t0;     // first token of the job in the packed arrays
-    int32_t s;      // prompt length
-    int32_t qt;     // query tile
-    int32_t group;  // head group: heads 8*group .. 8*group+7
+    int32_t t0;        // first token of the job in the packed arrays
+    int32_t s;         // prompt length
+    int32_t qt_group;  // query tile | head group << 16 (heads 8*group .. 8*group+7)
+    int32_t job;       // index of the job in this launch
 };
 constexpr int kPfMaxItems = 262144;  // entries the pool's work list holds
 
-// Builds the work list of a launch (one workgroup).  offs[J+1], J <= 1024; G head groups.
+// Builds the work list of a launch (one workgroup).  offs[J+1], J <= 1024; G head groups; prompts
+// of at most 65535 query tiles.
 // items[0].t0 receives the entry count, entries follow from items[1].  A job whose offsets
 // decrease or leave [0, total_tokens] raises the flag and gets no entry.
 __global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t *__restrict__ offs, int32_t J,
@@ -140,16 +141,24 @@ __global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t
         PfItem it;
         it.t0 = s_t0[j];
         it.s = s_len[j];
-        it.group = rem / tiles;
-        it.qt = tiles - 1 - rem % tiles;
+        it.qt_group = (tiles - 1 - rem % tiles) | ((rem / tiles) << 16);
+        it.job = j;
         items[1 + e] = it;
     }
 }
 
-template <typename E, int D>
+//
+// kWrite: the call is the whole initialization phase of its jobs and also fills their cache
+// blocks: token t of job j goes to slot t % 16 of block table[j][t / 16].  The workgroup whose
+// query rows ARE the tokens of a key tile (query tile kt / 2) writes that tile while it has it
+// staged: keys from LDS with 16 lanes over the 16 slots of a block, so that a wave writes 1 KiB
+// of the pool's [d/8][slot][8] key order in one piece, values from the staging registers row by row.
+template <typename E, int D, bool kWrite>
 __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     const char *__restrict__ q, const char *__restrict__ k, const char *__restrict__ v,
-    const PfItem *__restrict__ items, float *__restrict__ out, int32_t H, float scale_log2e)
+    const PfItem *__restrict__ items, float *__restrict__ out, int32_t H, float scale_log2e,
+    char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride, int32_t num_blocks,
+    int32_t *__restrict__ err)
 {
     constexpr int kKStride = D * 2 + 16;  // bytes per staged key row: 16 rows hit 16 different bank groups
     constexpr int kVStride = D * 2 + 32;  // bytes per staged value row: 4 rows of a transpose read do
@@ -170,10 +179,10 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     const int seq = blockIdx.x / kXcds;
     if (seq >= items[0].t0) return;
     const PfItem item = items[1 + seq];
-    const int h = item.group * kXcds + blockIdx.x % kXcds;
+    const int h = (item.qt_group >> 16) * kXcds + blockIdx.x % kXcds;
     if (h >= H) return;
     const long long t0 = item.t0;
-    const int s = item.s, qt = item.qt;
+    const int s = item.s, qt = item.qt_group & 0xffff;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, hh = lane >> 5;
@@ -242,8 +251,41 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
         __syncthreads();  // every wave is done reading the previous tile
         store_tile();
         __syncthreads();
-        if (kt + 1 < nkt) load_tile(kt + 1);  // in flight while this tile is computed
         const int key0 = kt * kPfKTile;
+        if (kWrite && (kt >> 1) == qt) {  // workgroup-uniform: this tile's tokens are this workgroup's rows
+            static_assert(kPfKTile % kBlockTokens == 0 && kPfQTile == 2 * kPfKTile, "tile shapes");
+            const size_t chunk = (size_t)kBlockTokens * D * 2;  // bytes of one head's keys (or values) in a block
+            const int32_t *trow = table + (size_t)item.job * table_stride;
+            // values: this thread's staging registers hold 16 bytes of row st_row (+ kRowsPerPass per pass)
+#pragma unroll
+            for (int p = 0; p < SP; ++p) {
+                const int pos = key0 + st_row + p * kRowsPerPass;
+                if (pos < s) {
+                    const int bid = pos / kBlockTokens < table_stride ? trow[pos / kBlockTokens] : -1;
+                    if ((uint32_t)bid < (uint32_t)num_blocks)
+                        *(u32x4 *)(pool + (size_t)bid * (2 * (size_t)H * chunk) + ((size_t)H + h) * chunk +
+                                   (size_t)(pos % kBlockTokens) * (D * 2) + st_chunk * 16) = vr[p];
+                    else if (st_chunk == 0 && h == 0) atomicOr(err, kErrBadBlock);
+                }
+            }
+            // keys: lane -> slot, so that 16 lanes fill the 256 contiguous bytes of one d/8 chunk
+            const int w_slot = threadIdx.x % kBlockTokens, w_rest = threadIdx.x / kBlockTokens;
+            constexpr int kPieces = kPfKTile * kChunks / kThreads;  // 16-byte pieces per thread
+#pragma unroll
+            for (int p = 0; p < kPieces; ++p) {
+                const int piece = w_rest + p * (kThreads / kBlockTokens);  // (block in tile, chunk)
+                const int blk = piece / kChunks, ch = piece % kChunks;
+                const int pos = key0 + blk * kBlockTokens + w_slot;
+                if (pos < s) {
+                    const int bid = pos / kBlockTokens < table_stride ? trow[pos / kBlockTokens] : -1;
+                    if ((uint32_t)bid < (uint32_t)num_blocks)
+                        *(u32x4 *)(pool + (size_t)bid * (2 * (size_t)H * chunk) + (size_t)h * chunk +
+                                   ((size_t)ch * kBlockTokens + w_slot) * 16) =
+                            *(const u32x4 *)(ks + (blk * kBlockTokens + w_slot) * kKStride + ch * 16);
+                }
+            }
+        }
+        if (kt + 1 < nkt) load_tile(kt + 1);  // in flight while this tile is computed
         // wave-uniform: the whole tile lies in this wave's future, or the wave has no row of the prompt
         if (key0 > row0 + 31 || row0 >= s) continue;
 

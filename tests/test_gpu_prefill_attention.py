@@ -154,3 +154,93 @@ def test_float_pools_are_refused():
         fs.fs_prefill_attention(pool, x, x, x, torch.tensor([0, 8], dtype=torch.int32, device="cuda"), x.clone())
     assert ei.value.status == fs.FS_ERR_UNSUPPORTED
     pool.close()
+
+
+# ---- the whole initialization phase in one launch: cache fill + attention ---------------
+def shuffled_tables(lens, block_size, spare, seed):
+    """Every job owns ceil(len/block) blocks drawn without order from a pool with `spare` extra."""
+    nblk = [(n + block_size - 1) // block_size for n in lens]
+    total = sum(nblk) + spare
+    ids = np.random.default_rng(seed).permutation(total).astype(np.int32)
+    W = max(max(nblk), 1)
+    table = np.full((len(lens), W), -1, dtype=np.int32)
+    at = 0
+    for j, nb in enumerate(nblk):
+        table[j, :nb] = ids[at:at + nb]
+        at += nb
+    return table, total
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f16", 64), ("bf16", 64)])
+def test_prefill_step_fills_the_cache_bit_exactly_and_matches_the_oracle(dtype, D):
+    import paper_2305_05920_amd as fs
+    from oracle.layout_model import PoolLayout
+    H = 3
+    lens = [1, 15, 16, 17, 63, 64, 65, 128, 129, 200, 0, 300]
+    print(f"[case] prefill step {dtype} D={D}", flush=True)
+    q, k, v, offs = make_prompts(dtype, lens, H, D, 21)
+    table, nb = shuffled_tables(lens, 16, 5, 22)
+    lay = PoolLayout(H, D, 16, 2)
+    sentinel = np.uint16(0x7FC1)
+    want = np.full((nb, lay.block_elems), sentinel, dtype=np.uint16)
+    for j, n in enumerate(lens):
+        lay.write_tokens(want, table[j], 0, k[offs[j]:offs[j + 1]], v[offs[j]:offs[j + 1]])
+    mem = hs.to_torch(dtype, np.full((nb, lay.block_elems), sentinel, dtype=np.uint16))
+    pool = fs.Pool(dtype, H, D, nb, device_mem=mem)
+    T = q.shape[0]
+    out = torch.full((T, H, D), float("nan"), dtype=torch.float32, device="cuda")
+    fs.fs_prefill_step(pool, torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda(),
+                       hs.to_torch(dtype, k), hs.to_torch(dtype, v), hs.to_torch(dtype, q), out)
+    torch.cuda.synchronize()
+    pool.check()
+    img = hs.from_torch(dtype, mem)
+    pool.close()
+    assert np.array_equal(img, want), "pool image differs from the layout model"
+    hs.assert_parity(out.cpu().numpy(), oracle_prompts(dtype, q, k, v, offs), f"prefill step {dtype} D={D}")
+
+
+def test_prefill_step_then_decode_steps_match_the_oracle():
+    # the two phases of a job back to back: prompts through fs_prefill_step, then three fused
+    # decode steps over the blocks it filled
+    import paper_2305_05920_amd as fs
+    H, D, dtype = 4, 128, "bf16"
+    lens = [37, 128, 5, 260]
+    q, k, v, offs = make_prompts(dtype, lens, H, D, 31)
+    table, nb = shuffled_tables([n + 3 for n in lens], 16, 2, 32)
+    pool = fs.Pool(dtype, H, D, nb)
+    d_table = torch.from_numpy(table).cuda()
+    out = torch.empty((q.shape[0], H, D), dtype=torch.float32, device="cuda")
+    fs.fs_prefill_step(pool, d_table, torch.from_numpy(offs).cuda(), hs.to_torch(dtype, k), hs.to_torch(dtype, v),
+                       hs.to_torch(dtype, q), out)
+    lc = oracle.LogicalCaches(dtype, H, D)
+    for j in range(len(lens)):
+        lc.add_job(np.ascontiguousarray(k[offs[j]:offs[j + 1]]), np.ascontiguousarray(v[offs[j]:offs[j + 1]]),
+                   spare=3)
+    rng = np.random.default_rng(33)
+    cur = np.array(lens, dtype=np.int32)
+    for stepno in range(3):
+        qn, kn, vn = (wl.f32_to_bf16_bits(rng.standard_normal((len(lens), H, D), dtype=np.float32)) for _ in range(3))
+        got = torch.empty((len(lens), H, D), dtype=torch.float32, device="cuda")
+        fs.fs_decode_step(pool, d_table, torch.from_numpy(cur).cuda(), hs.to_torch(dtype, kn), hs.to_torch(dtype, vn),
+                          hs.to_torch(dtype, qn), got)
+        torch.cuda.synchronize()
+        pool.check()
+        ref = lc.decode_step(kn, vn, qn)
+        hs.assert_parity(got.cpu().numpy(), ref, f"decode step {stepno} after prefill step")
+        cur += 1
+    pool.close()
+
+
+def test_prefill_step_flags_a_table_that_is_too_short():
+    import paper_2305_05920_amd as fs
+    H, D = 2, 64
+    q, k, v, offs = make_prompts("bf16", [40], H, D, 41)
+    table = np.array([[0, 1]], dtype=np.int32)                 # 32 tokens of room for 40
+    pool = fs.Pool("bf16", H, D, 4)
+    out = torch.empty((40, H, D), dtype=torch.float32, device="cuda")
+    fs.fs_prefill_step(pool, torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda(), hs.to_torch("bf16", k),
+                       hs.to_torch("bf16", v), hs.to_torch("bf16", q), out)
+    torch.cuda.synchronize()
+    with pytest.raises(fs.FsError):
+        pool.check()
+    pool.close()
