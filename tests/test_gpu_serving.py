@@ -1,5 +1,6 @@
 """Token-granularity preemptive serving end to end on the GPU: the skip-join MLFQ
-scheduler admits a different ragged batch every iteration, the proactive cache manager
+scheduler admits a different ragged batch every iteration, new jobs run their initialization
+phase (cache fill and prompt attention in one launch), the proactive cache manager
 moves the blocks of waiting jobs to host memory and back on a side stream while the
 decode step of the running batch executes, and every generated token's attention output
 is checked against the CPU oracle's logical caches (which know nothing of blocks,
@@ -42,6 +43,7 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
     waiting, done = [], set()
     last_ran, preempted = {}, set()
     checked = 0
+    prompt_rows = 0
     it = 0
     while len(done) < njobs:
         assert it < 600, "serving loop does not terminate"
@@ -57,15 +59,25 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
         kv.start_swaps(runnable, want_free=len(batch) - len(runnable) + len(waiting))
         first = [j for j in runnable if length[j] == 0]
         decode = [j for j in runnable if length[j] > 0]
-        for j in first:                                          # initialization phase: the prompt's KV
-            n = int(prompts[j])
-            K[j][:n], V[j][:n] = rand_bits((n, H, D)), rand_bits((n, H, D))
-            fs.fs_kv_prefill(pool, torch.from_numpy(kv.table_rows([j])).cuda(),
-                             torch.zeros(1, dtype=torch.int32, device="cuda"),
-                             torch.tensor([0, n], dtype=torch.int32, device="cuda"), n,
-                             hs.to_torch("bf16", K[j][:n]), hs.to_torch("bf16", V[j][:n]))
-            kv.advance(j, n)
-            length[j] = n
+        if first:                                                # initialization phase, all new jobs in one launch
+            ns = [int(prompts[j]) for j in first]
+            offs = np.zeros(len(first) + 1, dtype=np.int32)
+            offs[1:] = np.cumsum(ns)
+            pq, pk, pv = (rand_bits((int(offs[-1]), H, D)) for _ in range(3))
+            pout = torch.full((int(offs[-1]), H, D), float("nan"), dtype=torch.float32, device="cuda")
+            fs.fs_prefill_step(pool, torch.from_numpy(kv.table_rows(first)).cuda(), torch.from_numpy(offs).cuda(),
+                               hs.to_torch("bf16", pk), hs.to_torch("bf16", pv), hs.to_torch("bf16", pq), pout)
+            torch.cuda.synchronize()
+            pgot = pout.cpu().numpy()
+            for r, j in enumerate(first):
+                a, b = int(offs[r]), int(offs[r + 1])
+                K[j][:ns[r]], V[j][:ns[r]] = pk[a:b], pv[a:b]
+                ref = oracle.prefill_attention_job(np.ascontiguousarray(pq[a:b]), np.ascontiguousarray(pk[a:b]),
+                                                   np.ascontiguousarray(pv[a:b]), "bf16")
+                hs.assert_parity(pgot[a:b], ref, f"iteration {it} prompt of job {j} ({ns[r]} tokens)")
+                prompt_rows += ns[r]
+                kv.advance(j, ns[r])
+                length[j] = ns[r]
         if decode:                                               # decoding phase: one fused step
             q, kn, vn = (rand_bits((len(decode), H, D)) for _ in range(3))
             lens_before = np.array([length[j] for j in decode], dtype=np.int32)
@@ -101,9 +113,10 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
             kv.release(j)
             done.add(j)
         it += 1
-    print(f"[serving] {it} iterations, {checked} decode outputs checked, {len(preempted)} jobs preempted, "
+    print(f"[serving] {it} iterations, {prompt_rows} prompt rows and {checked} decode outputs checked, "
+          f"{len(preempted)} jobs preempted, "
           f"{kv.swapped_out_blocks} blocks swapped out, {kv.swapped_in_blocks} swapped in", flush=True)
-    assert checked == int((outputs - 1).sum())
+    assert checked == int((outputs - 1).sum()) and prompt_rows == int(prompts.sum())
     assert kv.swapped_out_blocks > 0 and kv.swapped_in_blocks > 0, "the test did not exercise swapping"
     assert preempted, "no job was ever preempted"
     assert len(kv.free_blocks) == pool.num_blocks and len(kv.free_slots) == pool.num_host_blocks
