@@ -345,6 +345,7 @@ def main():
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-swap-overlap", action="store_true", help="skip the steps timed beside block swaps")
     ap.add_argument("--no-prefill", action="store_true", help="skip the initialization-phase measurement")
     ap.add_argument("--only-prefill", action="store_true", help="measure the initialization phase alone")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -398,7 +399,8 @@ def main():
                    "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
                                   "kernel_ms": kt_f,
                                   "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
-            res["swap_overlap"] = swap_overlap(torch, reps, max(50, steps // 2), max(5, warmup // 2))
+            if not args.no_swap_overlap:
+                res["swap_overlap"] = swap_overlap(torch, reps, max(50, steps // 2), max(5, warmup // 2))
             if not args.no_graph:
                 try:
                     res["ms_per_step_graph"] = graph_ms(torch, reps, steps)
