@@ -243,7 +243,28 @@ def cpu_baseline(reps, budget_s=12.0):
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix-core peak
 
 
-def prefill_phase(fs, torch, wl, cfg, reps, log):
+def prefill_cpu_baseline(wl, cfg, budget_s=8.0):
+    """The oracle's prompt attention on a bounded sample of the same workload: one prompt of the
+    preset's median length, as many heads as fit the time budget (single thread)."""
+    import oracle
+    lens = wl.job_lens(cfg, wl.seed_for(cfg.index, 0)).astype(np.int64)
+    n = int(np.sort(lens)[len(lens) // 2])
+    rng = np.random.default_rng(wl.seed_for(cfg.index, 0))
+    conv = wl.f32_to_bf16_bits if cfg.dtype == "bf16" else wl.f32_to_f16_bits
+    q, k, v = (conv(rng.standard_normal((n, cfg.num_heads, cfg.head_dim), dtype=np.float32)) for _ in range(3))
+    heads, spent = 0, 0.0
+    while heads < cfg.num_heads and spent < budget_s:
+        t0 = time.perf_counter()
+        oracle.prefill_attention_job(q, k, v, cfg.dtype, heads=(heads, heads + 1))
+        spent += time.perf_counter() - t0
+        heads += 1
+    flops = 4.0 * cfg.head_dim * heads * n * (n + 1) / 2
+    return {"value": flops / spent / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": f"one prompt of {n} tokens (the preset's median), {heads} of {cfg.num_heads} heads, "
+                      f"{spent:.1f}s of CPU work", "prompt_tokens_per_s": n * heads / cfg.num_heads / spent}
+
+
+def prefill_phase(fs, torch, wl, cfg, reps, log, with_cpu=True):
     """Initialization phase on the preset's shape: the jobs' lengths taken as prompt lengths,
     packed q, k, v [T][H][D]; fs_kv_prefill writes the cache blocks, fs_prefill_attention
     computes the causal attention of every prompt token.  Kernel times from launch-attached
@@ -309,7 +330,8 @@ def prefill_phase(fs, torch, wl, cfg, reps, log):
                             "unit": "TFLOP/s", "frac": flops / (attn_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                             "traffic": None, "kernel": "fs_prefill_attn_kernel", "flops_per_launch": flops,
                             "alg_bytes_per_launch": hbm_bytes,
-                            "alg_gbps": hbm_bytes / (attn_ms * 1e-3) / 1e9}}
+                            "alg_gbps": hbm_bytes / (attn_ms * 1e-3) / 1e9},
+               "cpu_baseline": prefill_cpu_baseline(wl, cfg) if with_cpu else None}
         log(json.dumps(res))
         return res
     finally:
@@ -423,7 +445,7 @@ def main():
 
     if args.only_prefill:
         cfg = wl.CONFIGS[args.config] if not args.dtype else wl.CONFIGS[args.config].scaled(dtype=args.dtype)
-        print(json.dumps(prefill_phase(fs, torch, wl, cfg, 20, log)), flush=True)
+        print(json.dumps(prefill_phase(fs, torch, wl, cfg, 20, log, not args.no_cpu_baseline)), flush=True)
         return
     main_res, base = measure(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
     others = []
@@ -468,7 +490,7 @@ def main():
         "other_workloads": others,
     }
     if not args.no_prefill:
-        line["prefill_phase"] = prefill_phase(fs, torch, wl, cfg, 20, log)
+        line["prefill_phase"] = prefill_phase(fs, torch, wl, cfg, 20, log, not args.no_cpu_baseline)
     print(json.dumps(line), flush=True)
 
 

@@ -244,3 +244,55 @@ def test_prefill_step_flags_a_table_that_is_too_short():
     with pytest.raises(fs.FsError):
         pool.check()
     pool.close()
+
+
+def test_initialization_phase_at_the_benchmarked_size_sampled():
+    # The workload bench.py times for the initialization phase: the headline preset's 32 lengths
+    # taken as prompts, 40 heads x 128, bf16 (18.6 k tokens), through fs_prefill_step with
+    # shuffled block tables.  The oracle recomputes sampled (token, head) rows one by one (a
+    # decode-style attention over the first i+1 tokens); every other row must be finite and
+    # inside the bound that holds for any attention output (|out| <= max |v| over the prompt);
+    # sampled blocks are read back through the C ABI against the layout model.
+    import paper_2305_05920_amd as fs
+    from oracle.layout_model import PoolLayout
+    cfg = wl.CONFIGS[1]
+    H, D, dtype = cfg.num_heads, cfg.head_dim, cfg.dtype
+    lens = wl.job_lens(cfg, wl.seed_for(cfg.index, 0)).tolist()
+    print(f"[case] initialization phase full size: {len(lens)} prompts, {sum(lens)} tokens", flush=True)
+    q, k, v, offs = make_prompts(dtype, lens, H, D, 51)
+    table, nb = shuffled_tables(lens, 16, 7, 52)
+    lay = PoolLayout(H, D, 16, 2)
+    T = q.shape[0]
+    with fs.Pool(dtype, H, D, nb) as pool:
+        out = torch.full((T, H, D), float("nan"), dtype=torch.float32, device="cuda")
+        fs.fs_prefill_step(pool, torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda(),
+                           hs.to_torch(dtype, k), hs.to_torch(dtype, v), hs.to_torch(dtype, q), out)
+        torch.cuda.synchronize()
+        pool.check()
+        got = out.cpu().numpy()
+        rng = np.random.default_rng(53)
+        for j in rng.choice(len(lens), size=6, replace=False):
+            for bi in {0, (lens[j] - 1) // 16, int(rng.integers(0, (lens[j] + 15) // 16))}:
+                blk = pool.read_block(int(table[j, bi]), np.uint16)[None]
+                n = min(16, lens[j] - bi * 16)
+                k1, v1 = lay.read_tokens(blk, np.zeros(1, dtype=np.int32), 0, n)
+                a = int(offs[j]) + bi * 16
+                assert np.array_equal(k1, k[a:a + n]) and np.array_equal(v1, v[a:a + n]), (j, bi)
+    assert np.isfinite(got).all()
+    for j in range(len(lens)):
+        a, b = int(offs[j]), int(offs[j + 1])
+        vmax = np.abs(wl.bf16_bits_to_f32(v[a:b])).max(axis=0)            # [H][D]
+        assert (np.abs(got[a:b]) <= vmax + 1e-6).all()
+    worst = 0.0
+    for _ in range(160):
+        j = int(rng.integers(len(lens)))
+        i, h = int(rng.integers(lens[j])), int(rng.integers(H))
+        a = int(offs[j])
+        ref = oracle.attention_job(np.ascontiguousarray(q[a + i]), np.ascontiguousarray(k[a:a + i + 1]),
+                                   np.ascontiguousarray(v[a:a + i + 1]), dtype, heads=(h, h + 1))[h]
+        err = np.abs(got[a + i, h] - ref).max()
+        rel = np.linalg.norm(got[a + i, h] - ref) / np.linalg.norm(ref)
+        worst = max(worst, err)
+        # the relative bar is stated for whole tensors; a single 128-element row gets some slack
+        assert err <= hs.MAX_ABS_TOL and rel <= 4 * hs.REL_L2_TOL, (j, i, h, err, rel)
+    print(f"[parity] initialization phase full size: worst sampled max_abs={worst:.3e}", flush=True)
