@@ -1,5 +1,7 @@
 """GPU parity of the prompt-phase attention (matrix-core kernel, called through the C ABI)
 against the CPU oracle's causal definition, prompt by prompt."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -296,3 +298,49 @@ def test_initialization_phase_at_the_benchmarked_size_sampled():
         # the relative bar is stated for whole tensors; a single 128-element row gets some slack
         assert err <= hs.MAX_ABS_TOL and rel <= 4 * hs.REL_L2_TOL, (j, i, h, err, rel)
     print(f"[parity] initialization phase full size: worst sampled max_abs={worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FS_RANDOM_SEEDS", "6"))))
+def test_random_prompt_batches_both_entry_points(seed):
+    # random job counts, head counts, head_dim, 2-byte dtype and length mixes (zeros included);
+    # the attention-only entry point and the fused initialization step against the oracle, the
+    # filled pool against the layout model
+    import paper_2305_05920_amd as fs
+    from oracle.layout_model import PoolLayout
+    rng = np.random.default_rng(2000 + seed)
+    D = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "f16"]))
+    H = int(rng.integers(1, 10))
+    J = int(rng.integers(1, 24))
+    mix = str(rng.choice(["short", "long", "mixed"]))
+    hi = {"short": 70, "long": 700, "mixed": 400}[mix]
+    lens = rng.integers(0, hi, size=J)
+    if mix == "mixed":
+        lens = np.where(rng.random(J) < 0.5, rng.integers(0, 20, size=J), lens)
+    lens = [int(n) for n in lens]
+    print(f"[case] random prompts seed {seed}: J={J} H={H} D={D} {dtype} mix={mix} tokens={sum(lens)}", flush=True)
+    if sum(lens) == 0:
+        lens[0] = 3
+    q, k, v, offs = make_prompts(dtype, lens, H, D, 3000 + seed)
+    ref = oracle_prompts(dtype, q, k, v, offs)
+    got = run_device(dtype, H, D, q, k, v, offs)
+    hs.assert_parity(got, ref, f"random prompts {seed} attention only")
+    table, nb = shuffled_tables(lens, 16, 3, 4000 + seed)
+    lay = PoolLayout(H, D, 16, 2)
+    sentinel = np.uint16(0x7FC1)
+    want = np.full((nb, lay.block_elems), sentinel, dtype=np.uint16)
+    for j in range(J):
+        lay.write_tokens(want, table[j], 0, k[offs[j]:offs[j + 1]], v[offs[j]:offs[j + 1]])
+    mem = hs.to_torch(dtype, np.full((nb, lay.block_elems), sentinel, dtype=np.uint16))
+    pool = fs.Pool(dtype, H, D, nb, device_mem=mem)
+    out = torch.full((q.shape[0], H, D), float("nan"), dtype=torch.float32, device="cuda")
+    fs.fs_prefill_step(pool, torch.from_numpy(table).cuda(), torch.from_numpy(offs).cuda(), hs.to_torch(dtype, k),
+                       hs.to_torch(dtype, v), hs.to_torch(dtype, q), out)
+    torch.cuda.synchronize()
+    pool.check()
+    img = hs.from_torch(dtype, mem)
+    pool.close()
+    assert np.array_equal(img, want), "pool image differs from the layout model"
+    fused = out.cpu().numpy()
+    hs.assert_parity(fused, ref, f"random prompts {seed} fused step")
+    assert np.array_equal(fused, got), "the fused step and the attention-only call differ"
