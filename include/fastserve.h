@@ -1,12 +1,14 @@
 /*
- * fastserve.h -- C ABI of the paged decode step for AMD MI355X (gfx950).
+ * fastserve.h -- C ABI of the paged attention iterations for AMD MI355X (gfx950).
  *
- * One decode iteration of token-granularity preemptive serving (FastServe,
+ * One iteration of token-granularity preemptive serving (FastServe,
  * arXiv 2305.05920): the scheduler admits a ragged batch of jobs (Section 3.2,
- * Algorithm 1), the engine appends every job's new key/value token to that
- * job's cache and runs the new token's masked self-attention over the whole
- * cache (Section 2.2), and the cache manager moves blocks of inactive jobs
- * between GPU memory and host memory (Section 4.2).
+ * Algorithm 1).  In the decoding phase the engine appends every job's new
+ * key/value token to that job's cache and runs the new token's masked
+ * self-attention over the whole cache; in the initialization phase (a job's
+ * first iteration) it fills the cache with all prompt tokens and runs their
+ * causal self-attention (Section 2.2).  The cache manager moves blocks of
+ * inactive jobs between GPU memory and host memory (Section 4.2).
  *
  * Conventions
  *   - Every function returns an fs_status (0 = FS_OK, negative = error) unless
