@@ -481,6 +481,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-swap-overlap", action="store_true", help="skip the steps timed beside block swaps")
+    ap.add_argument("--no-warm-cache", action="store_true", help="skip the steps repeated on one pool")
     ap.add_argument("--no-prefill", action="store_true", help="skip the initialization-phase measurement")
     ap.add_argument("--only-prefill", action="store_true", help="measure the initialization phase alone")
     ap.add_argument("--no-serving-run", action="store_true", help="skip the multi-iteration scheduler-driven run")
@@ -536,7 +537,7 @@ def main():
                    "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
                                   "kernel_ms": kt_f,
                                   "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
-            if idx == args.config:
+            if idx == args.config and not args.no_warm_cache:
                 res["ms_per_step_warm_cache"] = time_steps_warm(torch, reps, steps, warmup)
             if not args.no_swap_overlap:
                 res["swap_overlap"] = swap_overlap(torch, reps, max(50, steps // 2), max(5, warmup // 2))
