@@ -344,3 +344,30 @@ def test_random_prompt_batches_both_entry_points(seed):
     fused = out.cpu().numpy()
     hs.assert_parity(fused, ref, f"random prompts {seed} fused step")
     assert np.array_equal(fused, got), "the fused step and the attention-only call differ"
+
+
+def test_very_long_prompt_sampled():
+    # one prompt of 20 000 tokens (157 query tiles, 313 key tiles for the last one) beside a short
+    # one; sampled rows against the oracle's decode-style attention over the first i+1 tokens
+    import paper_2305_05920_amd as fs
+    H, D, dtype = 2, 128, "bf16"
+    lens = [20000, 77]
+    print("[case] prefill attention, 20 000-token prompt", flush=True)
+    q, k, v, offs = make_prompts(dtype, lens, H, D, 61)
+    got = run_device(dtype, H, D, q, k, v, offs)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(62)
+    rows = [0, 1, 127, 128, 19999, 19998, 12345] + [int(x) for x in rng.integers(0, 20000, size=40)]
+    worst = 0.0
+    for i in rows:
+        h = int(rng.integers(H))
+        ref = oracle.attention_job(np.ascontiguousarray(q[i]), np.ascontiguousarray(k[:i + 1]),
+                                   np.ascontiguousarray(v[:i + 1]), dtype, heads=(h, h + 1))[h]
+        err = np.abs(got[i, h] - ref).max()
+        worst = max(worst, err)
+        assert err <= hs.MAX_ABS_TOL, (i, h, err)
+    a = int(offs[1])
+    ref = oracle.prefill_attention_job(np.ascontiguousarray(q[a:]), np.ascontiguousarray(k[a:]),
+                                       np.ascontiguousarray(v[a:]), dtype)
+    hs.assert_parity(got[a:], ref, "short prompt beside the long one")
+    print(f"[parity] 20 000-token prompt: worst sampled max_abs={worst:.3e}", flush=True)
