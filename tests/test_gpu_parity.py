@@ -496,3 +496,40 @@ def test_kernel_timing_records():
         assert run.pool.profile_collect()["attention"]["launches"] == 0
     finally:
         run.close()
+
+
+def test_two_pools_on_two_streams_at_once_match_their_serial_results():
+    # a pool is not thread-safe, but different pools may run at the same time: the decode step of
+    # two batches on two streams, launched back to back without a wait in between, ten times
+    # over, must give each batch bit for bit what it gets alone
+    import paper_2305_05920_amd as fs
+    cases = [hs.make_case(wl.CONFIGS[1].scaled(num_jobs=12, num_heads=8), 0),
+             hs.make_case(wl.CONFIGS[3].scaled(num_jobs=10, num_heads=6), 1)]
+    alone = []
+    for c in cases:
+        run = hs.DeviceRun(c)
+        try:
+            run.append()
+            alone.append(run.attention())
+        finally:
+            run.close()
+    runs = [hs.DeviceRun(c) for c in cases]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    try:
+        torch.cuda.synchronize()
+        for rep in range(10):
+            for run, st in zip(runs, streams):
+                if rep == 0:
+                    fs.fs_kv_append(run.pool, run.table, run.lens_before, run.k_new, run.v_new, stream=st)
+                fs.fs_decode_attention(run.q, run.pool, run.table, run.lens, run.out, stream=st)
+            if rep % 3 == 2:
+                torch.cuda.synchronize()
+                for run, want in zip(runs, alone):
+                    assert np.array_equal(run.out.cpu().numpy(), want), f"repetition {rep}"
+        torch.cuda.synchronize()
+        for run, want in zip(runs, alone):
+            run.pool.check()
+            assert np.array_equal(run.out.cpu().numpy(), want)
+    finally:
+        for run in runs:
+            run.close()
