@@ -533,3 +533,47 @@ def test_two_pools_on_two_streams_at_once_match_their_serial_results():
     finally:
         for run in runs:
             run.close()
+
+
+def test_graph_replays_of_both_step_forms_match_the_eager_results():
+    # The step is captured into a HIP graph (as a serving loop would, to shed launch overhead) in
+    # both forms and replayed several times, with eager work of the library and synchronisations
+    # between the replays; every replay must reproduce the eager output bit for bit.  (The library
+    # clears nothing with memset nodes: all scratch is written by its kernels before it is read.)
+    import paper_2305_05920_amd as fs
+    case = hs.make_case(wl.CONFIGS[1].scaled(num_jobs=10, num_heads=8), 2)
+    other = hs.make_case(wl.CONFIGS[2].scaled(num_jobs=16, num_heads=4), 0)
+    eager_two = hs.DeviceRun(case)
+    eager_two.append()
+    want_two = eager_two.attention()
+    eager_two.close()
+    eager_fused = hs.DeviceRun(case)
+    want_fused = eager_fused.fused_step()
+    eager_fused.close()
+    a, b, c = hs.DeviceRun(case), hs.DeviceRun(case), hs.DeviceRun(other)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                      # warm-up outside capture
+            a.append()
+            fs.fs_decode_attention(a.q, a.pool, a.table, a.lens, a.out)
+            fs.fs_decode_step(b.pool, b.table, b.lens_before, b.k_new, b.v_new, b.q, b.out)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fs.fs_kv_append(a.pool, a.table, a.lens_before, a.k_new, a.v_new)
+            fs.fs_decode_attention(a.q, a.pool, a.table, a.lens, a.out)
+            fs.fs_decode_step(b.pool, b.table, b.lens_before, b.k_new, b.v_new, b.q, b.out)
+        for rep in range(4):
+            a.out.fill_(float("nan"))
+            b.out.fill_(float("nan"))
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(a.out.cpu().numpy(), want_two), f"two-call form, replay {rep}"
+            assert np.array_equal(b.out.cpu().numpy(), want_fused), f"fused form, replay {rep}"
+            c.append()                                     # eager work between the replays
+            c.attention()
+            a.pool.check(), b.pool.check(), c.pool.check()
+    finally:
+        a.close(), b.close(), c.close()
