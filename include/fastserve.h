@@ -244,7 +244,7 @@ int fs_profile_enable(fs_pool *pool, int32_t enable);
 int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
 
 /* Named integer knobs for sweeps: "wgs_per_cu" (persistent attention workgroups per
- * compute unit, 1..8, default 1), "max_workgroups" (cap on that grid, 0 = none) and "swap_engine"
+ * compute unit, 1..8; 0 = default: 1 for fs_decode_attention, 2 for fs_decode_step), "max_workgroups" (cap on that grid, 0 = none) and "swap_engine"
  * (see fs_pool_offload); readable
  * also: "num_cus", "max_jobs_per_launch".  Unknown name or out-of-range value ->
  * FS_ERR_INVALID_ARG. */

@@ -886,9 +886,10 @@ struct fs_pool {
     int elem_bytes = 2;
     float scale = 0.f;
     int max_jobs = 1024;
-    // persistent workgroups per CU of the attention grid.  One is enough to saturate HBM (more
-    // did not raise the measured rate) and leaves the fewest partial results to merge.
-    int wgs_per_cu = 1;
+    // persistent workgroups per CU of the attention grid; 0 = the measured best: one for the
+    // plain kernel (enough to saturate HBM, fewest partial results to merge), two for the
+    // fused variant (its pair ends stall a wave, a second workgroup fills in).
+    int wgs_per_cu = 0;
     int max_workgroups = 0;  // optional cap on that grid (0 = none)
     // 0: one hipMemcpyAsync (copy engine) per run of consecutive blocks; 1: copy kernel.
     // The copy engine is the default: the attention grid is persistent and sized to fill
@@ -974,7 +975,7 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     // one unit = one 64-token step of one (job, head); no more waves than units can exist
     const long long units_bound = (long long)J * sh.num_heads * ceil_div(max_len, kStepTokens);
     long long wgs = (units_bound + kWavesPerWg - 1) / kWavesPerWg;
-    const long long persistent = (long long)p->num_cus * p->wgs_per_cu;
+    const long long persistent = (long long)p->num_cus * (p->wgs_per_cu > 0 ? p->wgs_per_cu : (kFused ? 2 : 1));
     if (wgs > persistent) wgs = persistent;
     if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
     if (wgs < 1) wgs = 1;
@@ -1375,7 +1376,7 @@ int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
         return FS_OK;
     }
     if (!std::strcmp(name, "wgs_per_cu")) {
-        if (value < 1 || value > kMaxWgsPerCu) return FS_ERR_INVALID_ARG;
+        if (value < 0 || value > kMaxWgsPerCu) return FS_ERR_INVALID_ARG;
         p->wgs_per_cu = value;
         return FS_OK;
     }
