@@ -170,6 +170,40 @@ def time_steps(torch, reps, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def time_step_chunks(torch, reps, chunks=20, per_chunk=20):
+    """Median and minimum of the step time over chunks of consecutive steps (each chunk timed like
+    the headline: wall clock between two synchronisations)."""
+    vals = []
+    for c in range(chunks):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(per_chunk):
+            reps.run_step(c * per_chunk + i)
+        torch.cuda.synchronize()
+        vals.append((time.perf_counter() - t0) * 1e3 / per_chunk)
+    return {"median_ms": float(np.median(vals)), "min_ms": float(np.min(vals)), "chunks": chunks,
+            "steps_per_chunk": per_chunk}
+
+
+def read_ceiling(fs, torch, nbytes=4 << 30, reps=5):
+    """Practical HBM read rate of this machine: a plain streaming read kernel over 4 GiB."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    src.zero_()
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    best = 0.0
+    for wgs in (2048, 4096, 8192):
+        fs.fs_stream_read(src, sink, wgs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fs.fs_stream_read(src, sink, wgs)
+        torch.cuda.synchronize()
+        best = max(best, nbytes * reps / (time.perf_counter() - t0) / 1e9)
+    del src
+    torch.cuda.empty_cache()
+    return best
+
+
 def time_steps_warm(torch, reps, steps, warmup):
     """The same step on ONE pool every time: its blocks stay in the 256 MB last-level cache
     between steps.  Reported beside the headline and labelled as such, never as the headline."""
@@ -538,6 +572,7 @@ def main():
                                   "kernel_ms": kt_f,
                                   "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
             if idx == args.config and not args.no_warm_cache:
+                res["ms_per_step_chunks"] = time_step_chunks(torch, reps)
                 res["ms_per_step_warm_cache"] = time_steps_warm(torch, reps, steps, warmup)
             if not args.no_swap_overlap:
                 res["swap_overlap"] = swap_overlap(torch, reps, max(50, steps // 2), max(5, warmup // 2))
@@ -554,6 +589,8 @@ def main():
                 diff = got.astype(np.float64) - ref
                 res["max_abs_err"] = float(np.abs(diff).max())
                 res["rel_l2_err"] = float(np.linalg.norm(diff) / np.linalg.norm(ref))
+                rows = np.linalg.norm(diff, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-300)
+                res["worst_row_rel_l2_err"] = float(rows.max())      # worst single (job, head) row
             for p in reps.pools:
                 p.check()
             log(json.dumps(res))
@@ -608,10 +645,16 @@ def main():
         "swap_overlap": main_res.get("swap_overlap"),
         "ms_per_step_graph": main_res.get("ms_per_step_graph"),
         "ms_per_step_warm_cache": main_res.get("ms_per_step_warm_cache"),
+        "ms_per_step_chunks": main_res.get("ms_per_step_chunks"),
         "max_abs_err": main_res.get("max_abs_err"),
         "rel_l2_err": main_res.get("rel_l2_err"),
+        "worst_row_rel_l2_err": main_res.get("worst_row_rel_l2_err"),
         "other_workloads": others,
     }
+    if not args.no_warm_cache:
+        ceil = read_ceiling(fs, torch)
+        line["roofline"]["practical_read_ceiling_gbps"] = ceil
+        line["roofline"]["frac_of_practical_ceiling"] = achieved / ceil
     if not args.no_serving_run:
         line["serving_run"] = serving_run(fs, torch, wl, cfg, log)
     if not args.no_prefill:
