@@ -62,14 +62,6 @@ struct PfMath<F16> {
     }
 };
 
-// q, k, v: [total_tokens][H][D] (2-byte elements), jobs packed back to back; offs[J+1].
-// out: [total_tokens][H][D] fp32.  `items` is the work list fs_prefill_plan_kernel wrote: entry
-// seq names a job (its first token and length), a group of 8 heads and a query tile.
-// Workgroup b runs on die b % 8 as that die's (b / 8)-th workgroup and serves entry b / 8 with
-// head 8 * group + b % 8.  The list walks the jobs from the longest down and, inside a
-// (job, head group), the query tiles from the last (most keys) to the first: the tiles of a
-// (job, head) so run at the same time on one die and find its keys and values in that
-// die's L2, and the long items start first.
 // One work-list entry: 128 query rows of 8 heads' worth of workgroups.
 struct PfItem {
     int32_t t0;        // first token of the job in the packed arrays
@@ -147,6 +139,14 @@ __global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t
     }
 }
 
+// q, k, v: [total_tokens][H][D] (2-byte elements), jobs packed back to back.
+// out: [total_tokens][H][D] fp32.  `items` is the work list fs_prefill_plan_kernel wrote: entry
+// seq names a job (its first token and length), a group of 8 heads and a query tile.
+// Workgroup b runs on die b % 8 as that die's (b / 8)-th workgroup and serves entry b / 8 with
+// head 8 * group + b % 8.  The list walks the jobs from the longest down and, inside a
+// (job, head group), the query tiles from the last (most keys) to the first: the tiles of a
+// (job, head) so run at the same time on one die and find its keys and values in that
+// die's L2, and the long items start first.
 //
 // kWrite: the call is the whole initialization phase of its jobs and also fills their cache
 // blocks: token t of job j goes to slot t % 16 of block table[j][t / 16].  The workgroup whose
