@@ -238,7 +238,10 @@ def serving_run(fs, torch, wl, cfg, log, njobs=96, max_batch=8, seed=7):
     live_tokens = int((prompts + outputs).sum())
     nblocks = max(W * 4, int(0.25 * live_tokens / 16))          # HBM holds a quarter of all caches: swapping is forced
     pool = fs.Pool(cfg.dtype, H, D, nblocks, num_host_blocks=int(live_tokens / 16) + njobs)
-    sched = Scheduler(6, 1.0, 1, 40.0, max_batch)
+    from paper_2305_05920_amd.profiler import IterationTimeProfile
+    prof_t = IterationTimeProfile(cfg.dtype, H, D, prompt_lengths=(16, 64, 256, 1024), cache_lengths=(16, 1024), reps=3)
+    q1 = prof_t.min_iteration_time()               # Section 4.1: the first quantum is the minimum iteration time
+    sched = Scheduler(6, q1, 1, 40.0 * q1, max_batch)
     kv = KVManager(pool, sched, W, reserve_idle_blocks=W)
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
@@ -259,7 +262,7 @@ def serving_run(fs, torch, wl, cfg, log, njobs=96, max_batch=8, seed=7):
         for j in list(waiting):
             if kv.blocks_needed(int(prompts[j]) + 1) + kv.reserve <= len(kv.free_blocks):
                 kv.admit(j, int(prompts[j]) + 1)
-                sched.add_job(j, float(prompts[j]) / 64.0, 1.0)
+                sched.add_job(j, prof_t.init_time(int(prompts[j])), prof_t.decode_time(int(prompts[j])))
                 waiting.remove(j)
         batch = sched.schedule()
         runnable = [j for j in batch if length[j] == 0 or kv.grow(j, 1)]
@@ -292,7 +295,8 @@ def serving_run(fs, torch, wl, cfg, log, njobs=96, max_batch=8, seed=7):
             tokens += 1
             if produced[j] == outputs[j]:
                 finished.append(j)
-        elapsed = max([float(prompts[j]) / 64.0 if j in first else 1.0 for j in runnable], default=1.0)
+        elapsed = max([prof_t.init_time(int(prompts[j])) if j in first else prof_t.decode_time(length[j])
+                       for j in runnable], default=q1)
         sched.complete_iteration(runnable, elapsed, finished)
         for j in finished:
             kv.release(j)
@@ -310,6 +314,7 @@ def serving_run(fs, torch, wl, cfg, log, njobs=96, max_batch=8, seed=7):
            "wall_s": wall, "job_tokens_per_s_wall": tokens / wall, "gpu_ms": gpu_ms,
            "job_tokens_per_s_gpu_time": tokens / (gpu_ms / 1e3) if gpu_ms else None,
            "blocks_swapped_out": kv.swapped_out_blocks, "blocks_swapped_in": kv.swapped_in_blocks,
+           "iteration_time_profile_ms": prof_t.as_dict(), "first_quantum_ms": q1,
            "note": "wall time is dominated by the Python driver of this loop (table upload and bookkeeping every iteration)"}
     sched.close()
     pool.close()

@@ -122,3 +122,21 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
     assert len(kv.free_blocks) == pool.num_blocks and len(kv.free_slots) == pool.num_host_blocks
     sched.close()
     pool.close()
+
+
+def test_iteration_time_profile_feeds_skip_join():
+    # the job profiler of Section 3.2 / 4.1, measured with the library's own kernels: first-iteration
+    # time grows with the prompt, and skip-join sends long prompts to lower-priority queues
+    from paper_2305_05920_amd.profiler import IterationTimeProfile
+    from paper_2305_05920_amd.sched import Scheduler
+    prof = IterationTimeProfile("bf16", 8, 128, prompt_lengths=(16, 128, 1024, 4096), cache_lengths=(16, 2048), reps=3)
+    t = [prof.init_time(s) for s in (16, 128, 1024, 4096, 8192)]
+    print("[profile]", prof.as_dict(), flush=True)
+    assert all(x > 0 for x in t) and t[3] > 2 * t[0] and t[4] > t[3]
+    assert prof.decode_time(2048) >= prof.decode_time(16) > 0
+    q1 = prof.min_iteration_time()
+    assert 0 < q1 <= min(t)
+    sched = Scheduler(8, q1, 1, 1e9, 4)
+    queues = [sched.add_job(i, prof.init_time(s), prof.decode_time(s)) for i, s in enumerate((16, 1024, 8192))]
+    sched.close()
+    assert queues[0] == 1 and queues[0] <= queues[1] <= queues[2] and queues[2] > 1
