@@ -7,13 +7,16 @@ side stream, so that the transfer of waiting jobs overlaps the decode kernels of
 running batch; the decode kernels see nothing of this but the block table.
 
 Blocks are owned by jobs in whole; a job is either resident (all its blocks in HBM) or
-swapped out (all its blocks in host slots).  ``reserve_idle_blocks`` HBM blocks are
+swapped out (all its blocks in host slots).  A model has one pool per layer; the manager
+takes them all (``layers``): block ids and host slots are shared by the layers, so one
+table serves every layer and a job's whole key-value tensor -- all layers, as the paper's
+cache size 4*l*h*(s+t) counts it -- moves together.  ``reserve_idle_blocks`` HBM blocks are
 kept free for new arrivals (Section 4.2, "Handling a burst of new jobs").
 """
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import Dict, List, Optional, Sequence
+from typing import Dict, List, Optional, Sequence, Union
 
 import numpy as np
 import torch
@@ -31,7 +34,13 @@ class JobBlocks:
 
 
 class KVManager:
-    def __init__(self, pool: Pool, sched: Scheduler, table_width: int, reserve_idle_blocks: int = 0):
+    def __init__(self, pool: Union[Pool, Sequence[Pool]], sched: Scheduler, table_width: int,
+                 reserve_idle_blocks: int = 0):
+        self.layers: List[Pool] = [pool] if isinstance(pool, Pool) else list(pool)
+        pool = self.layers[0]
+        if any(p.num_blocks != pool.num_blocks or p.num_host_blocks != pool.num_host_blocks or
+               p.block_size != pool.block_size for p in self.layers):
+            raise ValueError("the layers' pools must have the same numbers of blocks and host slots")
         self.pool, self.sched = pool, sched
         self.B = pool.block_size
         self.W = table_width
@@ -86,8 +95,9 @@ class KVManager:
     def _offload(self, job_id: int) -> None:
         jb = self.jobs[job_id]
         slots = [self.free_slots.pop() for _ in jb.blocks]
-        fs_pool_offload(self.pool, jb.blocks, slots, stream=self.side)
-        self.swapped_out_blocks += len(slots)
+        for layer in self.layers:
+            fs_pool_offload(layer, jb.blocks, slots, stream=self.side)
+        self.swapped_out_blocks += len(slots) * len(self.layers)
         self._pending_free.extend(jb.blocks)      # reusable once the copy has run
         jb.host_slots, jb.blocks, jb.resident = slots, [], False
         self.sched.set_ready(job_id, False)
@@ -95,8 +105,9 @@ class KVManager:
     def _upload(self, job_id: int) -> None:
         jb = self.jobs[job_id]
         blocks = [self.free_blocks.pop() for _ in jb.host_slots]
-        fs_pool_upload(self.pool, jb.host_slots, blocks, stream=self.side)
-        self.swapped_in_blocks += len(blocks)
+        for layer in self.layers:
+            fs_pool_upload(layer, jb.host_slots, blocks, stream=self.side)
+        self.swapped_in_blocks += len(blocks) * len(self.layers)
         self._pending_slots.extend(jb.host_slots)
         self._pending_ready.append(job_id)         # schedulable once the copy has run
         jb.blocks, jb.host_slots, jb.resident = blocks, [], True

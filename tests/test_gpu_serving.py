@@ -1,8 +1,9 @@
 """Token-granularity preemptive serving end to end on the GPU: the skip-join MLFQ
 scheduler admits a different ragged batch every iteration, new jobs run their initialization
-phase (cache fill and prompt attention in one launch), the proactive cache manager
-moves the blocks of waiting jobs to host memory and back on a side stream while the
-decode step of the running batch executes, and every generated token's attention output
+phase (cache fill and prompt attention in one launch per layer), the proactive cache manager
+moves the blocks of waiting jobs -- of both layers of the two-layer model, which share one
+block table -- to host memory and back on a side stream while the decode step of the running
+batch executes, and every generated token's attention output
 is checked against the CPU oracle's logical caches (which know nothing of blocks,
 preemption or swapping)."""
 import numpy as np
@@ -29,15 +30,18 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
     outputs = rng.integers(3, 12, size=njobs)
     arrival = np.sort(rng.integers(0, 12, size=njobs))
     # HBM pool of 36 blocks (576 tokens) for ~1800 tokens of live cache: swapping is forced
-    pool = fs.Pool("bf16", H, D, 36, num_host_blocks=160)
+    NL = 2                                     # two layers: one pool each, one table for both
+    pools = [fs.Pool("bf16", H, D, 36, num_host_blocks=160) for _ in range(NL)]
+    pool = pools[0]
     sched = Scheduler(4, 1.0, 1, 6.0, 4)
-    kv = KVManager(pool, sched, W, reserve_idle_blocks=4)
+    kv = KVManager(pools, sched, W, reserve_idle_blocks=4)
 
     def rand_bits(shape):
         return wl.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
 
-    K = {j: np.zeros((256, H, D), np.uint16) for j in range(njobs)}      # logical caches (oracle side)
-    V = {j: np.zeros((256, H, D), np.uint16) for j in range(njobs)}
+    # logical caches (oracle side), one per layer and job
+    K = {(l, j): np.zeros((256, H, D), np.uint16) for l in range(NL) for j in range(njobs)}
+    V = {(l, j): np.zeros((256, H, D), np.uint16) for l in range(NL) for j in range(njobs)}
     length = {j: 0 for j in range(njobs)}
     produced = {j: 0 for j in range(njobs)}
     waiting, done = [], set()
@@ -59,46 +63,54 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
         kv.start_swaps(runnable, want_free=len(batch) - len(runnable) + len(waiting))
         first = [j for j in runnable if length[j] == 0]
         decode = [j for j in runnable if length[j] > 0]
-        if first:                                                # initialization phase, all new jobs in one launch
+        if first:                                                # initialization phase, all new jobs in one launch per layer
             ns = [int(prompts[j]) for j in first]
             offs = np.zeros(len(first) + 1, dtype=np.int32)
             offs[1:] = np.cumsum(ns)
-            pq, pk, pv = (rand_bits((int(offs[-1]), H, D)) for _ in range(3))
-            pout = torch.full((int(offs[-1]), H, D), float("nan"), dtype=torch.float32, device="cuda")
-            fs.fs_prefill_step(pool, torch.from_numpy(kv.table_rows(first)).cuda(), torch.from_numpy(offs).cuda(),
-                               hs.to_torch("bf16", pk), hs.to_torch("bf16", pv), hs.to_torch("bf16", pq), pout)
-            torch.cuda.synchronize()
-            pgot = pout.cpu().numpy()
+            d_table, d_offs = torch.from_numpy(kv.table_rows(first)).cuda(), torch.from_numpy(offs).cuda()
+            for l in range(NL):
+                pq, pk, pv = (rand_bits((int(offs[-1]), H, D)) for _ in range(3))
+                pout = torch.full((int(offs[-1]), H, D), float("nan"), dtype=torch.float32, device="cuda")
+                fs.fs_prefill_step(pools[l], d_table, d_offs, hs.to_torch("bf16", pk), hs.to_torch("bf16", pv),
+                                   hs.to_torch("bf16", pq), pout)
+                torch.cuda.synchronize()
+                pgot = pout.cpu().numpy()
+                for r, j in enumerate(first):
+                    a, b = int(offs[r]), int(offs[r + 1])
+                    K[l, j][:ns[r]], V[l, j][:ns[r]] = pk[a:b], pv[a:b]
+                    ref = oracle.prefill_attention_job(np.ascontiguousarray(pq[a:b]), np.ascontiguousarray(pk[a:b]),
+                                                       np.ascontiguousarray(pv[a:b]), "bf16")
+                    hs.assert_parity(pgot[a:b], ref, f"iteration {it} layer {l} prompt of job {j} ({ns[r]} tokens)")
+                    prompt_rows += ns[r]
             for r, j in enumerate(first):
-                a, b = int(offs[r]), int(offs[r + 1])
-                K[j][:ns[r]], V[j][:ns[r]] = pk[a:b], pv[a:b]
-                ref = oracle.prefill_attention_job(np.ascontiguousarray(pq[a:b]), np.ascontiguousarray(pk[a:b]),
-                                                   np.ascontiguousarray(pv[a:b]), "bf16")
-                hs.assert_parity(pgot[a:b], ref, f"iteration {it} prompt of job {j} ({ns[r]} tokens)")
-                prompt_rows += ns[r]
                 kv.advance(j, ns[r])
                 length[j] = ns[r]
-        if decode:                                               # decoding phase: one fused step
-            q, kn, vn = (rand_bits((len(decode), H, D)) for _ in range(3))
+        layer_out = []
+        if decode:                                               # decoding phase: one fused step per layer
             lens_before = np.array([length[j] for j in decode], dtype=np.int32)
-            out = torch.full((len(decode), H, D), float("nan"), dtype=torch.float32, device="cuda")
-            fs.fs_decode_step(pool, torch.from_numpy(kv.table_rows(decode)).cuda(),
-                              torch.from_numpy(lens_before).cuda(), hs.to_torch("bf16", kn),
-                              hs.to_torch("bf16", vn), hs.to_torch("bf16", q), out)
+            d_table, d_lens = torch.from_numpy(kv.table_rows(decode)).cuda(), torch.from_numpy(lens_before).cuda()
+            for l in range(NL):
+                q, kn, vn = (rand_bits((len(decode), H, D)) for _ in range(3))
+                out = torch.full((len(decode), H, D), float("nan"), dtype=torch.float32, device="cuda")
+                fs.fs_decode_step(pools[l], d_table, d_lens, hs.to_torch("bf16", kn), hs.to_torch("bf16", vn),
+                                  hs.to_torch("bf16", q), out)
+                layer_out.append((q, kn, vn, out))
         kv.finish_swaps()
         torch.cuda.synchronize()
-        pool.check()
+        for p in pools:
+            p.check()
         if decode:
-            got = out.cpu().numpy()
-            for r, j in enumerate(decode):
-                K[j][length[j]], V[j][length[j]] = kn[r], vn[r]
+            for l, (q, kn, vn, out) in enumerate(layer_out):
+                got = out.cpu().numpy()
+                for r, j in enumerate(decode):
+                    K[l, j][length[j]], V[l, j][length[j]] = kn[r], vn[r]
+                    ref = oracle.attention_job(q[r], K[l, j], V[l, j], "bf16", length=length[j] + 1)
+                    err = np.abs(got[r] - ref).max()
+                    assert err <= hs.MAX_ABS_TOL, (it, l, j, err)
+                    checked += 1
+            for j in decode:
                 length[j] += 1
                 kv.advance(j, 1)
-                ref = oracle.attention_job(q[r], K[j], V[j], "bf16", length=length[j])
-                hs.assert_parity(got[r], ref, f"iteration {it} job {j} length {length[j]}") if checked % 25 == 0 else None
-                err = np.abs(got[r] - ref).max()
-                assert err <= hs.MAX_ABS_TOL, (it, j, err)
-                checked += 1
         finished = []
         for j in runnable:
             produced[j] += 1
@@ -116,12 +128,13 @@ def test_serving_loop_with_preemption_and_swapping_matches_oracle():
     print(f"[serving] {it} iterations, {prompt_rows} prompt rows and {checked} decode outputs checked, "
           f"{len(preempted)} jobs preempted, "
           f"{kv.swapped_out_blocks} blocks swapped out, {kv.swapped_in_blocks} swapped in", flush=True)
-    assert checked == int((outputs - 1).sum()) and prompt_rows == int(prompts.sum())
+    assert checked == NL * int((outputs - 1).sum()) and prompt_rows == NL * int(prompts.sum())
     assert kv.swapped_out_blocks > 0 and kv.swapped_in_blocks > 0, "the test did not exercise swapping"
     assert preempted, "no job was ever preempted"
     assert len(kv.free_blocks) == pool.num_blocks and len(kv.free_slots) == pool.num_host_blocks
     sched.close()
-    pool.close()
+    for p in pools:
+        p.close()
 
 
 def test_iteration_time_profile_feeds_skip_join():
