@@ -25,6 +25,33 @@ from . import Pool, fs_pool_offload, fs_pool_upload
 from .sched import Scheduler
 
 
+class ArrivalReserve:
+    """How many HBM blocks to keep idle for new jobs (Section 4.2, "Handling a burst of new
+    jobs": the number of idle slots follows the historical arrival pattern, more for more
+    frequent bursts).  The paper gives no formula; this one keeps the demand -- blocks asked
+    for by the jobs that arrived in one iteration -- of the last `window` iterations and
+    reserves a high quantile of it, never less than `floor` blocks."""
+
+    def __init__(self, window: int = 64, quantile: float = 0.9, floor: int = 0):
+        if window < 1 or not 0.0 <= quantile <= 1.0 or floor < 0:
+            raise ValueError("window >= 1, 0 <= quantile <= 1, floor >= 0")
+        self.window, self.quantile, self.floor = window, quantile, floor
+        self.history: List[int] = []
+
+    def observe(self, blocks_demanded: int) -> None:
+        """Record one iteration (0 when nothing arrived)."""
+        self.history.append(int(blocks_demanded))
+        if len(self.history) > self.window:
+            del self.history[0]
+
+    def blocks(self) -> int:
+        if not self.history:
+            return self.floor
+        ordered = sorted(self.history)
+        k = min(len(ordered) - 1, int(np.ceil(self.quantile * len(ordered))) - 1 if self.quantile > 0 else 0)
+        return max(self.floor, ordered[max(k, 0)])
+
+
 @dataclass
 class JobBlocks:
     length: int = 0                                         # tokens cached
@@ -44,13 +71,21 @@ class KVManager:
         self.pool, self.sched = pool, sched
         self.B = pool.block_size
         self.W = table_width
-        self.reserve = reserve_idle_blocks
+        self.reserve = reserve_idle_blocks          # blocks kept free for new arrivals; see observe_arrivals
+        self.arrival_reserve: Optional[ArrivalReserve] = None
         self.free_blocks: List[int] = list(range(pool.num_blocks - 1, -1, -1))
         self.free_slots: List[int] = list(range(pool.num_host_blocks - 1, -1, -1))
         self.jobs: Dict[int, JobBlocks] = {}
         self.side = torch.cuda.Stream()
         self.swapped_out_blocks = 0      # statistics
         self.swapped_in_blocks = 0
+
+    def observe_arrivals(self, blocks_demanded: int) -> None:
+        """Once per iteration: the blocks the jobs that arrived in it ask for.  With an
+        ArrivalReserve attached (``arrival_reserve``), the reserve follows the arrival history."""
+        if self.arrival_reserve is not None:
+            self.arrival_reserve.observe(blocks_demanded)
+            self.reserve = min(self.arrival_reserve.blocks(), self.pool.num_blocks // 2)
 
     # -- allocation ---------------------------------------------------------------------
     def blocks_needed(self, tokens: int) -> int:
