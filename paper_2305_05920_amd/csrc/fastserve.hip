@@ -745,52 +745,83 @@ __global__ __launch_bounds__(kThreads) void fs_kv_append_kernel(
 }
 
 // ------------------------------------------------------------------------------------
-// Bulk KV write: one thread moves one 16-byte vector of K and one of V of one
-// packed token; the owning job is found by bisection of token_offsets.
+// Bulk KV write.  A workgroup takes 16 consecutive packed tokens and a chunk of heads
+// (128 16-byte vectors per token).  Values go straight through: 16 lanes read one
+// 256-byte row and write it as one row of the pool's [slot][d] order.  Keys pass through
+// LDS so that both sides are whole rows: they are read like the values and written with
+// 16 lanes across the 16 tokens, which fill the 16 slots of one d/8 chunk of the pool's
+// [d/8][slot][8] key order when the tokens sit in one block.  The owning job of a packed
+// token is found by bisection of token_offsets, once per token and workgroup.
 // ------------------------------------------------------------------------------------
+constexpr int kFillVecs = 128;  // 16-byte vectors per token a workgroup moves (heads x vectors per head)
+
 template <int EB>
 __global__ __launch_bounds__(kThreads) void fs_kv_prefill_kernel(
     char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride,
     const int32_t *__restrict__ starts, const int32_t *__restrict__ offs, int32_t J, int32_t H,
-    int32_t D, int32_t num_blocks, long long total_tokens, const char *__restrict__ k,
+    int32_t D, int32_t num_blocks, long long total_tokens, int32_t head_chunks, const char *__restrict__ k,
     const char *__restrict__ v, int32_t *__restrict__ err)
 {
-    const int nk = D * EB / 16;
-    const long long per_tok = (long long)H * nk;
-    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
-    if (idx >= total_tokens * per_tok) return;
-    const long long tok = idx / per_tok;
-    const int rem = (int)(idx - tok * per_tok);
-    const int h = rem / nk, vec = rem - h * nk;
-    int lo = 0, hi = J;  // last job with offs[job] <= tok
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if ((long long)offs[mid] <= tok) lo = mid; else hi = mid;
+    constexpr int kRow = kFillVecs * 16 + 16;  // LDS bytes per token: 16 tokens hit 16 different bank groups
+    __shared__ __attribute__((aligned(16))) char tile[kBlockTokens * kRow];
+    __shared__ int s_bid[kBlockTokens], s_slot[kBlockTokens];
+    const int nk = D * EB / 16;            // vectors per (token, head)
+    const int hc = kFillVecs / nk;         // heads per workgroup
+    const long long group = blockIdx.x / head_chunks;
+    const int h0 = (int)(blockIdx.x % head_chunks) * hc;
+    const int heads = (H - h0) < hc ? (H - h0) : hc;
+    const int vecs = heads * nk;           // vectors per token this workgroup moves (<= 128)
+    if (threadIdx.x < kBlockTokens) {
+        const long long tok = group * kBlockTokens + threadIdx.x;
+        int bid = -1, slot = 0;
+        if (tok < total_tokens) {
+            int lo = 0, hi = J;  // last job with offs[job] <= tok
+            while (hi - lo > 1) {
+                int mid = (lo + hi) >> 1;
+                if ((long long)offs[mid] <= tok) lo = mid; else hi = mid;
+            }
+            const int j = lo;
+            const long long in_job = tok - offs[j];
+            const long long pos = (long long)starts[j] + in_job;
+            if (in_job < 0 || tok >= (long long)offs[j + 1] || pos < 0 || pos / kBlockTokens >= table_stride) {
+                if (h0 == 0) atomicOr(err, kErrBadLen);
+            } else {
+                bid = table[(size_t)j * table_stride + pos / kBlockTokens];
+                if ((uint32_t)bid >= (uint32_t)num_blocks) {
+                    if (h0 == 0) atomicOr(err, kErrBadBlock);
+                    bid = -1;
+                }
+                slot = (int)(pos % kBlockTokens);
+            }
+        }
+        s_bid[threadIdx.x] = bid;
+        s_slot[threadIdx.x] = slot;
     }
-    const int j = lo;
-    const long long in_job = tok - offs[j];
-    if (in_job < 0 || tok >= (long long)offs[j + 1]) {
-        if (rem == 0) atomicOr(err, kErrBadLen);
-        return;
-    }
-    const long long pos = (long long)starts[j] + in_job;
-    if (pos < 0 || pos / kBlockTokens >= table_stride) {
-        if (rem == 0) atomicOr(err, kErrBadLen);
-        return;
-    }
-    const int bid = table[(size_t)j * table_stride + pos / kBlockTokens];
-    if ((uint32_t)bid >= (uint32_t)num_blocks) {
-        if (rem == 0) atomicOr(err, kErrBadBlock);
-        return;
-    }
-    const int slot = (int)(pos % kBlockTokens);
+    __syncthreads();
     const size_t chunk = (size_t)kBlockTokens * D * EB;
-    char *blk = pool + (size_t)bid * (2 * (size_t)H * chunk);
-    const size_t src = (size_t)idx * 16;
-    const u32x4 kv = *(const u32x4 *)(k + src);
-    const u32x4 vv = *(const u32x4 *)(v + src);
-    *(u32x4 *)(blk + (size_t)h * chunk + ((size_t)vec * kBlockTokens + slot) * 16) = kv;
-    *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
+    const size_t block_bytes = 2 * (size_t)H * chunk;
+    const size_t tok_bytes = (size_t)H * nk * 16;
+    // rows in: token t, vector x (of this head chunk) by thread t * vecs + x, x fastest
+    for (int i = threadIdx.x; i < kBlockTokens * vecs; i += kThreads) {
+        const int t = i / vecs, x = i - t * vecs;
+        const int bid = s_bid[t];
+        if (bid < 0) continue;
+        const size_t src = (size_t)(group * kBlockTokens + t) * tok_bytes + ((size_t)h0 * nk + x) * 16;
+        *(u32x4 *)(tile + t * kRow + x * 16) = *(const u32x4 *)(k + src);
+        const int h = h0 + x / nk, vec = x % nk;
+        *(u32x4 *)(pool + (size_t)bid * block_bytes + ((size_t)H + h) * chunk + (size_t)s_slot[t] * D * EB +
+                   (size_t)vec * 16) = *(const u32x4 *)(v + src);
+    }
+    __syncthreads();
+    // keys out: token fastest
+    for (int i = threadIdx.x; i < kBlockTokens * vecs; i += kThreads) {
+        const int t = i % kBlockTokens, x = i / kBlockTokens;
+        const int bid = s_bid[t];
+        if (bid < 0) continue;
+        const int h = h0 + x / nk, vec = x % nk;
+        *(u32x4 *)(pool + (size_t)bid * block_bytes + (size_t)h * chunk + ((size_t)vec * kBlockTokens + s_slot[t]) * 16) =
+            *(const u32x4 *)(tile + t * kRow + x * 16);
+    }
 }
 
 #include "prefill_attention.hpp"
@@ -1160,16 +1191,18 @@ int fs_kv_prefill(fs_pool *p, const int32_t *table, int32_t stride, const int32_
     if (!on_pool_device(p)) return FS_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     const int H = p->cfg.num_heads, D = p->cfg.head_dim;
-    const long long vecs = (long long)total_tokens * H * (D * p->elem_bytes / 16);
-    const long long wgs = (vecs + kThreads - 1) / kThreads;
+    const int nk = D * p->elem_bytes / 16;                 // vectors per (token, head)
+    const int hc = kFillVecs / nk;                          // heads per workgroup
+    const int head_chunks = (H + hc - 1) / hc;
+    const long long wgs = ((long long)total_tokens + kBlockTokens - 1) / kBlockTokens * head_chunks;
     if (wgs > 0x7fffffffLL) return FS_ERR_INVALID_ARG;
     if (p->elem_bytes == 2)
         launch_kernel(p, FS_KERNEL_PREFILL, fs_kv_prefill_kernel<2>, dim3((unsigned)wgs), s, p->mem, table, stride,
-                      starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, (const char *)k,
+                      starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, head_chunks, (const char *)k,
                       (const char *)v, p->err);
     else
         launch_kernel(p, FS_KERNEL_PREFILL, fs_kv_prefill_kernel<4>, dim3((unsigned)wgs), s, p->mem, table, stride,
-                      starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, (const char *)k,
+                      starts, offs, J, H, D, p->cfg.num_blocks, (long long)total_tokens, head_chunks, (const char *)k,
                       (const char *)v, p->err);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }

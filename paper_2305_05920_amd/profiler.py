@@ -36,16 +36,20 @@ class IterationTimeProfile:
         table = torch.arange(nblk, dtype=torch.int32, device="cuda").reshape(1, nblk)
         with Pool(dtype, H, D, nblk) as pool:
             def timed(fn) -> float:
+                # median over single calls: one slow outlier (first use of a kernel, a clock ramp)
+                # must not end up in the table
                 for _ in range(2):
                     fn()
                 torch.cuda.synchronize()
-                pool.profile_enable(True)
+                vals = []
                 for _ in range(reps):
+                    pool.profile_enable(True)
                     fn()
-                torch.cuda.synchronize()
-                prof = pool.profile_collect()
-                pool.profile_enable(False)
-                return sum(r["ms"] for r in prof.values()) / reps
+                    torch.cuda.synchronize()
+                    prof = pool.profile_collect()
+                    pool.profile_enable(False)
+                    vals.append(sum(r["ms"] for r in prof.values()))
+                return float(np.median(vals))
 
             self.init_ms = []
             for s in self.prompt_lengths.astype(int):
