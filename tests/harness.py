@@ -13,7 +13,7 @@ import fs_workload as wl
 import oracle
 from oracle.layout_model import PoolLayout
 
-# spec tolerance for attention outputs (bf16 KV, fp32 accumulation)
+# tolerance for attention outputs against the fp64 oracle (bf16 KV, fp32 accumulation)
 MAX_ABS_TOL = 1e-2
 REL_L2_TOL = 5e-3
 
