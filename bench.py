@@ -521,6 +521,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-swap-overlap", action="store_true", help="skip the steps timed beside block swaps")
     ap.add_argument("--no-warm-cache", action="store_true", help="skip the steps repeated on one pool")
+    ap.add_argument("--no-merge-in-kernel", action="store_true",
+                    help="skip the steps timed with the combine merged into the attention kernel")
     ap.add_argument("--no-prefill", action="store_true", help="skip the initialization-phase measurement")
     ap.add_argument("--only-prefill", action="store_true", help="measure the initialization phase alone")
     ap.add_argument("--no-serving-run", action="store_true", help="skip the multi-iteration scheduler-driven run")
@@ -576,6 +578,19 @@ def main():
                    "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
                                   "kernel_ms": kt_f,
                                   "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
+            if not args.no_merge_in_kernel:
+                # the same two step forms with the cut pairs merged by the attention kernel
+                # itself (no combine launch); the library's default is the combine launch
+                for p in reps.pools:
+                    p.set_param("merge_in_kernel", 1)
+                reps.fused = True
+                ms_mf = time_steps(torch, reps, steps, warmup)
+                reps.fused = False
+                ms_m = time_steps(torch, reps, steps, warmup)
+                kt_m = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
+                for p in reps.pools:
+                    p.set_param("merge_in_kernel", 0)
+                res["merge_in_kernel"] = {"ms_per_step": ms_m, "fused_ms_per_step": ms_mf, "kernel_ms": kt_m}
             if idx == args.config and not args.no_warm_cache:
                 res["ms_per_step_chunks"] = time_step_chunks(torch, reps)
                 res["ms_per_step_warm_cache"] = time_steps_warm(torch, reps, steps, warmup)
@@ -647,6 +662,7 @@ def main():
         "cpu_baseline": base,
         "kernel_ms": main_res["kernel_ms"],
         "fused_step": main_res["fused_step"],
+        "merge_in_kernel": main_res.get("merge_in_kernel"),
         "swap_overlap": main_res.get("swap_overlap"),
         "ms_per_step_graph": main_res.get("ms_per_step_graph"),
         "ms_per_step_warm_cache": main_res.get("ms_per_step_warm_cache"),

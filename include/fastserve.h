@@ -243,10 +243,17 @@ int fs_profile_enable(fs_pool *pool, int32_t enable);
  * (host arrays), then forgets the records. */
 int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
 
-/* Named integer knobs for sweeps: "wgs_per_cu" (persistent attention workgroups per
- * compute unit, 1..8; 0 = default: 1 for fs_decode_attention, 2 for fs_decode_step), "max_workgroups" (cap on that grid, 0 = none) and "swap_engine"
- * (see fs_pool_offload); readable
- * also: "num_cus", "max_jobs_per_launch".  Unknown name or out-of-range value ->
+/* Named integer knobs for sweeps:
+ *   "wgs_per_cu"       persistent attention workgroups per compute unit, 1..8; 0 = default:
+ *                      1 for fs_decode_attention, 2 for fs_decode_step;
+ *   "max_workgroups"   cap on that grid, 0 = none;
+ *   "swap_engine"      see fs_pool_offload;
+ *   "merge_in_kernel"  0 (default): a (job, head) pair whose cache was split over several
+ *                      waves is merged by a combine launch after the attention kernel;
+ *                      1: by the attention kernel itself -- the last wave to finish its share
+ *                      of such a pair merges it, no second launch.  Same arithmetic in the
+ *                      same order, hence the same bits in `out`.
+ * Readable also: "num_cus", "max_jobs_per_launch".  Unknown name or out-of-range value ->
  * FS_ERR_INVALID_ARG. */
 int fs_pool_set_param(fs_pool *pool, const char *name, int32_t value);
 int fs_pool_get_param(const fs_pool *pool, const char *name, int32_t *value);

@@ -177,6 +177,7 @@ struct AttnShape {
     int32_t table_stride;
     int32_t num_blocks;
     float scale_log2e;
+    int32_t merge;  // 1: the partition pass merges cut pairs itself (no combine launch follows)
 };
 
 enum : int32_t { kErrBadBlock = 1, kErrBadLen = 2 };
@@ -190,6 +191,52 @@ __device__ __forceinline__ long long range_lo(long long w, long long S, long lon
 // the wave that owns unit u
 __device__ __forceinline__ long long wave_of_unit(long long u, long long S, long long nw) {
     return ((u + 1) * nw + S - 1) / S - 1;
+}
+
+// Merge of one (job, head) pair whose units [u0, u0 + steps) were cut across several waves:
+//   M = max m_i, out = sum_i 2^(m_i-M) acc_i / sum_i 2^(m_i-M) l_i
+// over the partials the waves left (the pair's first wave in its slot 1, every later one in
+// its slot 0), walked in wave order; when there are more waves than units some ranges are
+// empty and are stepped over.  One wave, lane l owning D/64 output columns.
+// kAgentLoads: the partials were written by other waves of the SAME launch; they are read
+// with agent-scope atomic loads, which no cache of this compute die may serve stale.
+template <int D, bool kAgentLoads>
+__device__ __forceinline__ void merge_pair(const float *part_acc, const float *part_ml, long long u0, int steps,
+                                           long long S, long long nw, float *o_row, int lane)
+{
+    constexpr int PER = D / 64;
+    auto ld = [](const float *p) -> float {
+        if (kAgentLoads) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return *p;
+    };
+    const long long wa = wave_of_unit(u0, S, nw);
+    float M = -INFINITY;
+    float acc[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+    float l = 0.f;
+    const long long u1 = u0 + steps;
+    long long w = wa;
+    for (long long u = u0; u < u1;) {
+        const size_t slot = (size_t)w * 2 + (w == wa ? 1 : 0);
+        const float m_p = ld(part_ml + slot * 2);
+        const float l_p = ld(part_ml + slot * 2 + 1);
+        const float M_new = fmaxf(M, m_p);
+        const float m_ref = (M_new == -INFINITY) ? 0.f : M_new;
+        const float keep = __builtin_amdgcn_exp2f(M - m_ref);
+        const float wgt = __builtin_amdgcn_exp2f(m_p - m_ref);
+        l = fmaf(wgt, l_p, l * keep);
+        const float *a = part_acc + slot * D + lane * PER;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) acc[i] = fmaf(wgt, ld(a + i), acc[i] * keep);
+        M = M_new;
+        u = range_lo(w + 1, S, nw);  // first unit past this wave's range
+        if (u < u1) w = wave_of_unit(u, S, nw);
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    float *o = o_row + lane * PER;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) o[i] = acc[i] * inv;
 }
 
 // ------------------------------------------------------------------------------------
@@ -210,8 +257,8 @@ template <typename E, int D, bool kFused>
 __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_partition_kernel(
     const uint32_t *__restrict__ q, const char *pool, char *pool_w, const char *__restrict__ k_new,
     const char *__restrict__ v_new, const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
-    float *__restrict__ out, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    int32_t *__restrict__ plan, int32_t *__restrict__ err, AttnShape sh
+    float *__restrict__ out, float *part_acc, float *part_ml,
+    int32_t *__restrict__ plan, int32_t *__restrict__ err, int32_t *pair_cnt, AttnShape sh
 #ifdef FS_TRACE
     , unsigned long long *__restrict__ trace_buf
 #endif
@@ -284,8 +331,18 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     }
     if (tid == kThreads - 1) s_base[J] = run;  // threads past the last job add 0: the total
     __syncthreads();
-    if (blockIdx.x == 0)
+    if (blockIdx.x == 0) {
         for (int j = tid; j <= J; j += kThreads) plan[j] = s_base[j];
+        if (!kFused && sh.merge) {
+            // no combine pass follows: a job without tokens gets its zeros here (rare; one
+            // thread per such job)
+            for (int j = tid; j < J; j += kThreads) {
+                if (s_base[j + 1] != s_base[j]) continue;
+                float4 *o = (float4 *)(out + (size_t)j * H * D);
+                for (int i = 0; i < H * D / 4; ++i) o[i] = float4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    }
 
     // ---- this wave's range of units ----
     const long long S = (long long)__builtin_amdgcn_readfirstlane(s_base[J]) * H;
@@ -336,10 +393,9 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         return __builtin_amdgcn_readfirstlane(n);
     };
 
-    // ---- the unit the range starts with: job by 64-ary search of the prefix sums ----
-    int j;
-    {
-        const int key = (int)(lo / H);  // s_base[j]*H <= lo  <=>  s_base[j] <= lo / H
+    // the job that unit u belongs to: 64-ary search of the prefix sums
+    auto job_of_unit = [&](long long u) -> int {
+        const int key = (int)(u / H);  // s_base[j]*H <= u  <=>  s_base[j] <= u / H
         const int look_stride = (J + 64) >> 6;
         int i1 = lane * look_stride;
         i1 = i1 < J ? i1 : J;
@@ -348,8 +404,10 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         int i2 = seg + lane;
         i2 = i2 < J ? i2 : J;
         const int c2 = __popcll(__ballot(s_base[i2] <= key));
-        j = __builtin_amdgcn_readfirstlane(seg + c2 - 1);
-    }
+        return __builtin_amdgcn_readfirstlane(seg + c2 - 1);
+    };
+    // ---- the unit the range starts with ----
+    int j = job_of_unit(lo);
     auto steps_of = [](int len) {
         const int n = (len + kStepTokens - 1) / kStepTokens;
         return (kFused && n == 0) ? 1 : n;
@@ -625,11 +683,23 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 } else {
                     const size_t slot = (size_t)gw * 2 + (k_begin > 0 ? 0 : 1);
                     float *o = part_acc + slot * D + (size_t)vc * X;
+                    if (sh.merge) {
+                        // read by another wave of this launch, possibly on another compute die:
+                        // agent-scope stores go through to memory instead of resting in this die's L2
 #pragma unroll
-                    for (int i = 0; i < X; ++i) o[i] = acc[i];
-                    if (lane == 0) {
-                        part_ml[slot * 2] = m_run;
-                        part_ml[slot * 2 + 1] = l_sum;
+                        for (int i = 0; i < X; ++i)
+                            __hip_atomic_store(o + i, acc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (lane == 0) {
+                            __hip_atomic_store(part_ml + slot * 2, m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(part_ml + slot * 2 + 1, l_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < X; ++i) o[i] = acc[i];
+                        if (lane == 0) {
+                            part_ml[slot * 2] = m_run;
+                            part_ml[slot * 2 + 1] = l_sum;
+                        }
                     }
                 }
             }
@@ -638,6 +708,60 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 #pragma unroll
             for (int i = 0; i < X; ++i) acc[i] = 0.f;
             k_begin = 0;
+        }
+    }
+    // ---- merge mode: the last wave to finish its share of a cut pair merges the pair ----
+    // Every wave that holds a share publishes it (release fence, then an agent-scope add of
+    // its unit count to the pair's counter, which lives at the index of the pair's first
+    // wave: a wave is the first wave of one cut pair at most).  The wave whose add completes
+    // the pair's step count is the last: acquire fence, merge, counter back to zero for the
+    // next launch.  No wave ever waits for another.
+    // Which pairs those are follows from the range alone: the pair unit lo lies in, if lo is
+    // not its first unit (this wave's slot 0), and the pair unit hi-1 lies in, if it began
+    // inside the range and goes on past it (slot 1).
+    if (sh.merge) {
+        bool cut_have[2];
+        int cut_mine[2], cut_steps[2], cut_jh[2];
+        long long cut_u0[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const long long uu = c ? hi - 1 : lo;
+            const int jj = job_of_unit(uu);
+            const int st = steps_of(__builtin_amdgcn_readfirstlane(s_len[jj]));
+            const int local = (int)(uu - (long long)__builtin_amdgcn_readfirstlane(s_base[jj]) * H);
+            const int hh = local / st, kk = local - hh * st;
+            cut_u0[c] = uu - kk;
+            cut_steps[c] = st;
+            cut_jh[c] = jj * H + hh;
+            if (c == 0) {
+                const long long last = cut_u0[0] + st - 1 < hi - 1 ? cut_u0[0] + st - 1 : hi - 1;
+                cut_have[0] = kk > 0;
+                cut_mine[0] = (int)(last - lo) + 1;
+            } else {
+                cut_have[1] = kk < st - 1 && cut_u0[1] >= lo;
+                cut_mine[1] = kk + 1;
+            }
+        }
+        // the partial stores above were agent-scope (written through); all that is left to do
+        // before the counter add is to wait until they have completed
+        if (cut_have[0] || cut_have[1]) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // for the compiler: stores stay above
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // for the machine: stores have completed
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            if (!cut_have[c]) continue;
+            const long long wa = c ? gw : wave_of_unit(cut_u0[c], S, nw);
+            int old = 0;
+            if (lane == 0)
+                old = __hip_atomic_fetch_add(pair_cnt + wa, cut_mine[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old + cut_mine[c] == cut_steps[c]) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // keeps the loads below behind the add
+                merge_pair<D, true>(part_acc, part_ml, cut_u0[c], cut_steps[c], S, nw,
+                                    out + (size_t)cut_jh[c] * D, lane);
+                if (lane == 0) __hip_atomic_store(pair_cnt + wa, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
     FS_TRACE_STAMP(5);
@@ -676,36 +800,8 @@ __global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
     }
     const long long S = (long long)plan[J] * H, nw = num_waves;
     const long long u0 = (long long)base * H + (long long)h * steps;
-    const long long wa = wave_of_unit(u0, S, nw), wb = wave_of_unit(u0 + steps - 1, S, nw);
-    if (wa == wb) return;
-    // Walk the waves whose ranges overlap the pair (when there are more waves than
-    // units some ranges are empty and are stepped over).  The first wave of the pair
-    // left slot 1, every later one slot 0.  Online merge, in wave order.
-    float M = -INFINITY;
-    float acc[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
-    float l = 0.f;
-    const long long u1 = u0 + steps;
-    long long w = wa;
-    for (long long u = u0; u < u1;) {
-        const size_t slot = (size_t)w * 2 + (w == wa ? 1 : 0);
-        const float m_p = part_ml[slot * 2];
-        const float M_new = fmaxf(M, m_p);
-        const float m_ref = (M_new == -INFINITY) ? 0.f : M_new;
-        const float keep = __builtin_amdgcn_exp2f(M - m_ref);
-        const float wgt = __builtin_amdgcn_exp2f(m_p - m_ref);
-        l = fmaf(wgt, part_ml[slot * 2 + 1], l * keep);
-        const float *a = part_acc + slot * D + lane * PER;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] = fmaf(wgt, a[i], acc[i] * keep);
-        M = M_new;
-        u = range_lo(w + 1, S, nw);  // first unit past this wave's range
-        if (u < u1) w = wave_of_unit(u, S, nw);
-    }
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) o[i] = acc[i] * inv;
+    if (wave_of_unit(u0, S, nw) == wave_of_unit(u0 + steps - 1, S, nw)) return;
+    merge_pair<D, false>(part_acc, part_ml, u0, steps, S, nw, out + (size_t)jh * D, lane);
 }
 
 // ------------------------------------------------------------------------------------
@@ -927,9 +1023,14 @@ struct fs_pool {
     // the machine, and workgroups of a copy kernel beside it displace some of its
     // workgroups (measured: +16 % to +80 % step time), whereas engine copies cost ~1 %.
     int swap_engine = 0;
+    // 1: the attention kernel merges the pairs that were cut across waves itself (the last
+    // wave to finish a pair does it); 0: a combine launch follows.  Off by default: the two
+    // forms were measured and the separate pass keeps the attention kernel shorter.
+    int merge_in_kernel = 0;
     int waves_cap = 0;       // waves the partial buffers are sized for
     float *part_acc = nullptr;
     float *part_ml = nullptr;
+    int32_t *pair_cnt = nullptr;  // merge mode: units done per cut pair, indexed by the pair's first wave; zero between launches
     int32_t *plan = nullptr;
     PfItem *pf_items = nullptr;  // work list of the prompt-attention launches: count, then entries
     int32_t *err = nullptr;
@@ -958,6 +1059,8 @@ int alloc_scratch(fs_pool *p) {
     const long long waves = (long long)p->num_cus * kMaxWgsPerCu * kWavesPerWg;
     if (hipMalloc((void **)&p->part_acc, (size_t)waves * 2 * D * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
     if (hipMalloc((void **)&p->part_ml, (size_t)waves * 2 * 2 * sizeof(float)) != hipSuccess) return FS_ERR_OOM;
+    if (hipMalloc((void **)&p->pair_cnt, (size_t)waves * sizeof(int32_t)) != hipSuccess) return FS_ERR_OOM;
+    if (hipMemset(p->pair_cnt, 0, (size_t)waves * sizeof(int32_t)) != hipSuccess) return FS_ERR_HIP;
     p->waves_cap = (int)waves;
 #ifdef FS_TRACE
     if (hipMalloc((void **)&p->trace, (size_t)waves * 8 * sizeof(unsigned long long)) != hipSuccess) return FS_ERR_OOM;
@@ -1003,6 +1106,7 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     sh.table_stride = stride;
     sh.num_blocks = p->cfg.num_blocks;
     sh.scale_log2e = p->scale * 1.4426950408889634f;
+    sh.merge = p->merge_in_kernel;
     // one unit = one 64-token step of one (job, head); no more waves than units can exist
     const long long units_bound = (long long)J * sh.num_heads * ceil_div(max_len, kStepTokens);
     long long wgs = (units_bound + kWavesPerWg - 1) / kWavesPerWg;
@@ -1014,12 +1118,13 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     launch_kernel(p, FS_KERNEL_ATTENTION, fs_attn_partition_kernel<E, D, kFused>, dim3((unsigned)wgs), s,
                   (const uint32_t *)q, (const char *)p->mem, kFused ? p->mem : (char *)nullptr,
                   (const char *)k_new, (const char *)v_new, table, lens, out, p->part_acc, p->part_ml, p->plan,
-                  p->err, sh
+                  p->err, p->pair_cnt, sh
 #ifdef FS_TRACE
                   , p->trace
 #endif
     );
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
+    if (sh.merge) return FS_OK;
     const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
     launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_kernel<D>, dim3((unsigned)cw), s,
                   (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
@@ -1113,6 +1218,7 @@ int fs_pool_destroy(fs_pool *p)
     if (p->host_mem) (void)hipHostFree(p->host_mem);
     if (p->part_acc) (void)hipFree(p->part_acc);
     if (p->part_ml) (void)hipFree(p->part_ml);
+    if (p->pair_cnt) (void)hipFree(p->pair_cnt);
     if (p->plan) (void)hipFree(p->plan);
     if (p->pf_items) (void)hipFree(p->pf_items);
     if (p->err) (void)hipFree(p->err);
@@ -1413,6 +1519,11 @@ int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
         p->wgs_per_cu = value;
         return FS_OK;
     }
+    if (!std::strcmp(name, "merge_in_kernel")) {
+        if (value < 0 || value > 1) return FS_ERR_INVALID_ARG;
+        p->merge_in_kernel = value;
+        return FS_OK;
+    }
     return FS_ERR_INVALID_ARG;
 }
 
@@ -1422,6 +1533,7 @@ int fs_pool_get_param(const fs_pool *p, const char *name, int32_t *value)
     if (!std::strcmp(name, "max_workgroups")) *value = p->max_workgroups;
     else if (!std::strcmp(name, "wgs_per_cu")) *value = p->wgs_per_cu;
     else if (!std::strcmp(name, "swap_engine")) *value = p->swap_engine;
+    else if (!std::strcmp(name, "merge_in_kernel")) *value = p->merge_in_kernel;
     else if (!std::strcmp(name, "num_cus")) *value = p->num_cus;
     else if (!std::strcmp(name, "max_jobs_per_launch")) *value = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
     else return FS_ERR_INVALID_ARG;
