@@ -711,11 +711,12 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         }
     }
     // ---- merge mode: the last wave to finish its share of a cut pair merges the pair ----
-    // Every wave that holds a share publishes it (release fence, then an agent-scope add of
-    // its unit count to the pair's counter, which lives at the index of the pair's first
-    // wave: a wave is the first wave of one cut pair at most).  The wave whose add completes
-    // the pair's step count is the last: acquire fence, merge, counter back to zero for the
-    // next launch.  No wave ever waits for another.
+    // Every wave that holds a share publishes it: its partial went out with agent-scope
+    // stores; once they have completed it adds its unit count (agent-scope atomic) to the
+    // pair's counter, which lives at the index of the pair's first wave (a wave is the first
+    // wave of one cut pair at most).  The wave whose add completes the pair's step count is
+    // the last: it reads the partials (agent-scope loads), merges, and sets the counter back
+    // to zero for the next launch.  No wave ever waits for another.
     // Which pairs those are follows from the range alone: the pair unit lo lies in, if lo is
     // not its first unit (this wave's slot 0), and the pair unit hi-1 lies in, if it began
     // inside the range and goes on past it (slot 1).
