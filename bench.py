@@ -186,12 +186,13 @@ def time_step_chunks(torch, reps, chunks=20, per_chunk=20):
 
 
 def read_ceiling(fs, torch, nbytes=4 << 30, reps=5):
-    """Practical HBM read rate of this machine: a plain streaming read kernel over 4 GiB."""
+    """Practical HBM read rate of this machine: a plain streaming read kernel (non-temporal loads,
+    like the decode kernel's cache reads) over 4 GiB, best of several grid sizes."""
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     src.zero_()
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     best = 0.0
-    for wgs in (2048, 4096, 8192):
+    for wgs in (256, 512, 8192, 16384):
         fs.fs_stream_read(src, sink, wgs)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
