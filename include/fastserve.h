@@ -245,7 +245,8 @@ int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
 
 /* Named integer knobs for sweeps:
  *   "wgs_per_cu"       persistent attention workgroups per compute unit, 1..8; 0 = default:
- *                      1 for fs_decode_attention, 2 for fs_decode_step;
+ *                      7 workgroups per 8 compute units for fs_decode_attention, 2 per
+ *                      compute unit for fs_decode_step;
  *   "max_workgroups"   cap on that grid, 0 = none;
  *   "swap_engine"      see fs_pool_offload;
  *   "merge_in_kernel"  0 (default): a (job, head) pair whose cache was split over several
