@@ -245,8 +245,9 @@ int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
 
 /* Named integer knobs for sweeps:
  *   "wgs_per_cu"       persistent attention workgroups per compute unit, 1..8; 0 = default:
- *                      7 workgroups per 8 compute units for fs_decode_attention, 2 per
- *                      compute unit for fs_decode_step;
+ *                      for fs_decode_attention one per compute unit, of which a batch with
+ *                      at least 8 steps of 64 tokens per wave uses 7 of every 8 (decided on
+ *                      the device); for fs_decode_step 2 per compute unit;
  *   "max_workgroups"   cap on that grid, 0 = none;
  *   "swap_engine"      see fs_pool_offload;
  *   "merge_in_kernel"  0 (default): a (job, head) pair whose cache was split over several

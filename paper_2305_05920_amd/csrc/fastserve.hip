@@ -185,6 +185,7 @@ struct AttnShape {
     int32_t num_blocks;
     float scale_log2e;
     int32_t merge;  // 1: the partition pass merges cut pairs itself (no combine launch follows)
+    int32_t trim;   // 1: long batches use 7 of every 8 workgroups (see active_workgroups)
 };
 
 enum : int32_t { kErrBadBlock = 1, kErrBadLen = 2 };
@@ -198,6 +199,17 @@ __device__ __forceinline__ long long range_lo(long long w, long long S, long lon
 // the wave that owns unit u
 __device__ __forceinline__ long long wave_of_unit(long long u, long long S, long long nw) {
     return ((u + 1) * nw + S - 1) / S - 1;
+}
+// Workgroups of a launch that take part in the split.  With `trim` (the plain kernel's
+// default grid) a batch of at least 8 units per wave is worked on by 7 of every 8
+// workgroups, the same number on every XCD; the others leave at once.  Long kernels stream
+// 1.5-2 % faster that way (the memory system is slightly oversubscribed by a workgroup on
+// every compute unit); short ones need every wave, because a wave's share is a few whole
+// units and one unit more or less is a large step.
+__device__ __forceinline__ int active_workgroups(long long S, int G, int trim)
+{
+    if (!trim || G < 8 * kXcds || S < 8LL * G * kWavesPerWg) return G;
+    return G * 7 / 8 / kXcds * kXcds;
 }
 
 // Merge of one (job, head) pair whose units [u0, u0 + steps) were cut across several waves:
@@ -353,14 +365,16 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 
     // ---- this wave's range of units ----
     const long long S = (long long)__builtin_amdgcn_readfirstlane(s_base[J]) * H;
-    const long long nw = (long long)gridDim.x * kWavesPerWg;
+    const int G = active_workgroups(S, gridDim.x, sh.trim);
+    const long long nw = (long long)G * kWavesPerWg;
     // Workgroup b runs on XCD b % 8 (round-robin dispatch).  Ranges are handed out
     // XCD-major, so that each XCD walks one contiguous eighth of the batch -- whole
     // jobs, hence every head and with it every memory channel in equal measure --
     // and keeps a job's table rows and queries in its own L2.
     long long gw;
     {
-        const int G = gridDim.x, b = blockIdx.x;
+        const int b = blockIdx.x;
+        if (b >= G) return;
         const int x = b % kXcds, idx = b / kXcds;
         // workgroups on XCDs before x: sum over y < x of ceil((G - y) / 8)
         const int full = G / kXcds, extra = G % kXcds;
@@ -790,7 +804,8 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 template <int D>
 __global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
     const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H, int32_t num_waves)
+    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H, int32_t workgroups,
+    int32_t trim)
 {
     constexpr int PER = D / 64;
     const int lane = threadIdx.x & 63;
@@ -806,7 +821,8 @@ __global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
         for (int i = 0; i < PER; ++i) o[i] = 0.f;
         return;
     }
-    const long long S = (long long)plan[J] * H, nw = num_waves;
+    const long long S = (long long)plan[J] * H;
+    const long long nw = (long long)active_workgroups(S, workgroups, trim) * kWavesPerWg;
     const long long u0 = (long long)base * H + (long long)h * steps;
     if (wave_of_unit(u0, S, nw) == wave_of_unit(u0 + steps - 1, S, nw)) return;
     merge_pair<D, false>(part_acc, part_ml, u0, steps, S, nw, out + (size_t)jh * D, lane);
@@ -1022,9 +1038,10 @@ struct fs_pool {
     int elem_bytes = 2;
     float scale = 0.f;
     int max_jobs = 1024;
-    // persistent workgroups per CU of the attention grid; 0 = the measured best: 7 workgroups
-    // per 8 CUs for the plain kernel (enough to saturate HBM, fewest partial results to merge),
-    // two per CU for the fused variant (its pair ends stall a wave, a second workgroup fills in).
+    // persistent workgroups per CU of the attention grid; 0 = the measured best: one per CU
+    // for the plain kernel (enough to saturate HBM, fewest partial results to merge; long
+    // batches leave every eighth of them idle), two per CU for the fused variant (its pair
+    // ends stall a wave, a second workgroup fills in).
     int wgs_per_cu = 0;
     int max_workgroups = 0;  // optional cap on that grid (0 = none)
     // 0: one hipMemcpyAsync (copy engine) per run of consecutive blocks; 1: copy kernel.
@@ -1119,16 +1136,12 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     // one unit = one 64-token step of one (job, head); no more waves than units can exist
     const long long units_bound = (long long)J * sh.num_heads * ceil_div(max_len, kStepTokens);
     long long wgs = (units_bound + kWavesPerWg - 1) / kWavesPerWg;
-    // Default grids (wgs_per_cu == 0), from sweeps on this GPU: the plain kernel streams
-    // fastest with a workgroup on 7 of every 8 compute units (224 of 256: 1.5-2 % faster than
-    // 256, which in turn beats anything larger); the fused kernel wants two per CU.
-    long long persistent;
-    if (p->wgs_per_cu > 0) persistent = (long long)p->num_cus * p->wgs_per_cu;
-    else if (kFused) persistent = (long long)p->num_cus * 2;
-    else {
-        persistent = (long long)p->num_cus * 7 / 8 / kXcds * kXcds;  // the same number on every XCD
-        if (persistent < kXcds) persistent = p->num_cus;
-    }
+    // Default grids (wgs_per_cu == 0), from sweeps on this GPU: one workgroup per compute
+    // unit for the plain kernel, of which long batches use 7 of every 8 (decided on the
+    // device, where the lengths are known); two per compute unit for the fused kernel.
+    const long long persistent =
+        (long long)p->num_cus * (p->wgs_per_cu > 0 ? p->wgs_per_cu : (kFused ? 2 : 1));
+    sh.trim = (p->wgs_per_cu == 0 && !kFused) ? 1 : 0;
     if (wgs > persistent) wgs = persistent;
     if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
     if (wgs < 1) wgs = 1;
@@ -1146,7 +1159,7 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
     launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_kernel<D>, dim3((unsigned)cw), s,
                   (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
-                  sh.num_heads, (int32_t)(wgs * kWavesPerWg));
+                  sh.num_heads, (int32_t)wgs, sh.trim);
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     return FS_OK;
 }
