@@ -277,6 +277,22 @@ def test_grid_size_does_not_change_the_result(wgs):
     hs.assert_parity(got, hs.oracle_step(case), f"max_workgroups={wgs}")
 
 
+@pytest.mark.parametrize("wgs_per_cu", [0, 1, 2])
+def test_default_and_explicit_persistent_grids_on_a_full_preset(wgs_per_cu):
+    # 0: the default grid, which on a batch of this size (12 units per wave) leaves every eighth
+    # workgroup idle; 1, 2: that many workgroups per compute unit, all of them working
+    case = hs.make_case(wl.CONFIGS[1], 1)
+    run = hs.DeviceRun(case)
+    try:
+        run.pool.set_param("wgs_per_cu", wgs_per_cu)
+        run.append()
+        got = run.attention(max_len_hint=int(case.step.lens.max()))
+        run.pool.check()
+    finally:
+        run.close()
+    hs.assert_parity(got, hs.oracle_step(case), f"wgs_per_cu={wgs_per_cu}")
+
+
 def test_step_plan_is_the_prefix_sum_of_64_token_steps():
     cfg = wl.CONFIGS[3].scaled(num_jobs=9, num_heads=4)
     lens = np.array([64, 65, 640, 641, 2048, 2047, 1, 1537, 300], dtype=np.int32)
