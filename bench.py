@@ -574,7 +574,8 @@ def main():
             ms = time_steps(torch, reps, steps, warmup)
             kt = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
             res = {"workload": cfg.name, "ms_per_step": ms, "job_tokens_per_s": cfg.num_jobs / (ms / 1e3),
-                   "kernel_ms": kt, "alg_bytes": reps.alg_bytes, "replicas": reps.R,
+                   "kernel_ms": kt, "alg_bytes": reps.alg_bytes, "sum_len": int(reps.step.total_tokens),
+                   "replicas": reps.R,
                    "attention_gbps": reps.alg_bytes / (kt["attention"] * 1e-3) / 1e9,
                    "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
                                   "kernel_ms": kt_f,
@@ -653,7 +654,7 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index}] {cfg.name}: {cfg.num_jobs} jobs, {cfg.num_heads} heads x "
-                               f"{cfg.head_dim}, {cfg.dtype}, block 16, sum(L)={int(main_res['alg_bytes'] // (2 * cfg.num_heads * cfg.head_dim * cfg.elem_bytes))}",
+                               f"{cfg.head_dim}, {cfg.dtype}, block 16, sum(L)={main_res['sum_len']}",
                    "step": "fs_kv_append + fs_decode_attention (partition pass + combine)",
                    "pool_replicas": main_res["replicas"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
