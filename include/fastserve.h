@@ -197,8 +197,9 @@ int fs_decode_attention(const void *q, fs_pool *pool, const int32_t *block_table
  *      paper's engine fuses operations into fewer kernels) ---------------------------
  * Same result as fs_kv_append(pool, table, stride, job_lens, J, k, v) followed by
  * fs_decode_attention over job_lens[j] + 1 tokens, in one kernel launch fewer: the
- * attention kernel takes the new token's key and value from k, v and writes them
- * into the pool itself.
+ * attention kernel takes the new token's key and value from k, v instead of the pool, and
+ * the rows are written into the pool by the launch that merges the partial results (or by
+ * the attention kernel itself, see "append_in_attention").
  *   job_lens: device int32 [num_jobs], tokens cached BEFORE this step (as for append)
  *   k, v, q:  device [num_jobs][H][D], pool dtype;  out: device float32 [num_jobs][H][D]
  *   max_len_hint: upper bound of max_j job_lens[j] + 1 (<= 0: table_stride*B)
@@ -250,6 +251,10 @@ int fs_profile_collect(fs_pool *pool, float *total_ms, int32_t *launches);
  *                      the device); for fs_decode_step 2 per compute unit;
  *   "max_workgroups"   cap on that grid, 0 = none;
  *   "swap_engine"      see fs_pool_offload;
+ *   "append_in_attention"  fs_decode_step only.  0 (default): the attention kernel takes the
+ *                      new tokens from k, v and leaves writing them into the pool to the launch
+ *                      that follows it (extra workgroups of the combine pass); 1: it writes
+ *                      them itself as it meets them.  Same pool bytes and same `out` either way;
  *   "merge_in_kernel"  0 (default): a (job, head) pair whose cache was split over several
  *                      waves is merged by a combine launch after the attention kernel;
  *                      1: by the attention kernel itself -- the last wave to finish its share

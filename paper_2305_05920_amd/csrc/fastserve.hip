@@ -270,8 +270,11 @@ __device__ __forceinline__ void merge_pair(const float *part_acc, const float *p
 // before the append and the units cover those pool-resident tokens (one unit at
 // least per job, so that a job with an empty cache is visited too).  The new token of
 // every job comes from k_new / v_new ([J][H][D], pool dtype): the wave that owns the
-// last unit of a (job, head) scores it, adds it to the softmax state and writes its
-// key and value row into the pool (slot `lens[j]` of the job).
+// last unit of a (job, head) scores it, adds it to the softmax state and -- if pool_w is
+// given -- writes its key and value row into the pool (slot `lens[j]` of the job).  With
+// pool_w null the rows are left to the pass that follows (fs_attn_combine_append_kernel):
+// sixteen 16-byte pieces per key row, mixed into the read stream here, cost more than
+// the same writes after it.
 template <typename E, int D, bool kFused>
 __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_partition_kernel(
     const uint32_t *__restrict__ q, const char *pool, char *pool_w, const char *__restrict__ k_new,
@@ -607,7 +610,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 xk = *(const u32x4 *)(k_new + row);
                 xv = *(const u32x4 *)(v_new + row);
             }
-            xbid = table[(size_t)j_cur * sh.table_stride + L_cur / kBlockTokens];
+            if (pool_w) xbid = table[(size_t)j_cur * sh.table_stride + L_cur / kBlockTokens];
         }
 
         // ---- the next unit's q and keys go in flight ----
@@ -677,7 +680,9 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 m_run = m_new;
                 const int pos = L_cur;  // = lens[j]: where the token goes
                 const int wb = __builtin_amdgcn_readfirstlane(xbid);
-                if ((uint32_t)wb >= (uint32_t)sh.num_blocks) {
+                if (!pool_w) {
+                    // the rows are written by the pass that follows this kernel
+                } else if ((uint32_t)wb >= (uint32_t)sh.num_blocks) {
                     if (lane == 0) atomicOr(err, kErrBadBlock);
                 } else if (lane < LPT) {
                     char *blk = pool_w + (size_t)wb * block_bytes;
@@ -802,15 +807,15 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 // Pairs that one wave finished are left alone; jobs without tokens get zeros.
 // ------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
-    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H, int32_t workgroups,
-    int32_t trim)
+__device__ __forceinline__ void combine_block(int block, const float *__restrict__ part_acc,
+                                              const float *__restrict__ part_ml, const int32_t *__restrict__ plan,
+                                              float *__restrict__ out, int32_t J, int32_t H, int32_t workgroups,
+                                              int32_t trim)
 {
     constexpr int PER = D / 64;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int jh = blockIdx.x * kWavesPerWg + wave;
+    const int jh = block * kWavesPerWg + wave;
     if (jh >= J * H) return;
     const int j = jh / H, h = jh - j * H;
     const int base = plan[j];
@@ -828,17 +833,26 @@ __global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
     merge_pair<D, false>(part_acc, part_ml, u0, steps, S, nw, out + (size_t)jh * D, lane);
 }
 
+template <int D>
+__global__ __launch_bounds__(kThreads) void fs_attn_combine_kernel(
+    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
+    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H, int32_t workgroups,
+    int32_t trim)
+{
+    combine_block<D>(blockIdx.x, part_acc, part_ml, plan, out, J, H, workgroups, trim);
+}
+
 // ------------------------------------------------------------------------------------
 // KV append: one thread moves one 16-byte vector of K and one of V.
 // ------------------------------------------------------------------------------------
 template <int EB>
-__global__ __launch_bounds__(kThreads) void fs_kv_append_kernel(
-    char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride,
+__device__ __forceinline__ void append_block(
+    int block, char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride,
     const int32_t *__restrict__ lens, int32_t J, int32_t H, int32_t D, int32_t num_blocks,
     const char *__restrict__ k, const char *__restrict__ v, int32_t *__restrict__ err)
 {
     const int nk = D * EB / 16;  // vectors per (token, head) row
-    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const long long idx = (long long)block * kThreads + threadIdx.x;
     if (idx >= (long long)J * H * nk) return;
     const int vec = (int)(idx % nk);
     const long long jh = idx / nk;
@@ -874,6 +888,33 @@ __global__ __launch_bounds__(kThreads) void fs_kv_append_kernel(
 // token is found by bisection of token_offsets, once per token and workgroup.
 // ------------------------------------------------------------------------------------
 constexpr int kFillVecs = 128;  // 16-byte vectors per token a workgroup moves (heads x vectors per head)
+
+
+template <int EB>
+__global__ __launch_bounds__(kThreads) void fs_kv_append_kernel(
+    char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride,
+    const int32_t *__restrict__ lens, int32_t J, int32_t H, int32_t D, int32_t num_blocks,
+    const char *__restrict__ k, const char *__restrict__ v, int32_t *__restrict__ err)
+{
+    append_block<EB>(blockIdx.x, pool, table, table_stride, lens, J, H, D, num_blocks, k, v, err);
+}
+
+// The second launch of fs_decode_step: the combine pass in workgroups [0, combine_blocks),
+// the append of the step's new tokens (which the attention kernel took from k_new / v_new
+// and did not write) in the workgroups after them.
+template <int D, int EB>
+__global__ __launch_bounds__(kThreads) void fs_attn_combine_append_kernel(
+    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
+    const int32_t *__restrict__ plan, float *__restrict__ out, int32_t J, int32_t H, int32_t workgroups,
+    int32_t trim, int32_t combine_blocks, char *__restrict__ pool, const int32_t *__restrict__ table,
+    int32_t table_stride, const int32_t *__restrict__ lens, int32_t num_blocks, const char *__restrict__ k,
+    const char *__restrict__ v, int32_t *__restrict__ err)
+{
+    if ((int)blockIdx.x < combine_blocks)
+        combine_block<D>(blockIdx.x, part_acc, part_ml, plan, out, J, H, workgroups, trim);
+    else
+        append_block<EB>(blockIdx.x - combine_blocks, pool, table, table_stride, lens, J, H, D, num_blocks, k, v, err);
+}
 
 template <int EB>
 __global__ __launch_bounds__(kThreads) void fs_kv_prefill_kernel(
@@ -1053,6 +1094,10 @@ struct fs_pool {
     // wave to finish a pair does it); 0: a combine launch follows.  Off by default: the two
     // forms were measured and the separate pass keeps the attention kernel shorter.
     int merge_in_kernel = 0;
+    // fs_decode_step, 1: the attention kernel writes the new tokens' rows into the pool as it
+    // meets them; 0 (default): the launch that follows it (the combine pass) does, in extra
+    // workgroups.  The sixteen 16-byte pieces of a key row cost more inside the read stream.
+    int append_in_attention = 0;
     int waves_cap = 0;       // waves the partial buffers are sized for
     float *part_acc = nullptr;
     float *part_ml = nullptr;
@@ -1146,8 +1191,11 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
     if (wgs < 1) wgs = 1;
     if (wgs * kWavesPerWg > p->waves_cap) return FS_ERR_INVALID_ARG;
+    // fs_decode_step: the new tokens' rows are written by the attention kernel itself only
+    // where no second launch follows (merge mode) or on request; otherwise by that launch
+    const bool write_in_kernel = kFused && (sh.merge || p->append_in_attention);
     launch_kernel(p, FS_KERNEL_ATTENTION, fs_attn_partition_kernel<E, D, kFused>, dim3((unsigned)wgs), s,
-                  (const uint32_t *)q, (const char *)p->mem, kFused ? p->mem : (char *)nullptr,
+                  (const uint32_t *)q, (const char *)p->mem, write_in_kernel ? p->mem : (char *)nullptr,
                   (const char *)k_new, (const char *)v_new, table, lens, out, p->part_acc, p->part_ml, p->plan,
                   p->err, p->pair_cnt, sh
 #ifdef FS_TRACE
@@ -1157,6 +1205,16 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     if (sh.merge) return FS_OK;
     const int cw = ceil_div(J * sh.num_heads, kWavesPerWg);
+    if (kFused && !write_in_kernel) {
+        const long long vecs = (long long)J * sh.num_heads * (D * E::kBytes / 16);
+        const long long aw = (vecs + kThreads - 1) / kThreads;
+        launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_append_kernel<D, E::kBytes>, dim3((unsigned)(cw + aw)), s,
+                      (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
+                      sh.num_heads, (int32_t)wgs, sh.trim, (int32_t)cw, p->mem, table, stride, lens,
+                      sh.num_blocks, (const char *)k_new, (const char *)v_new, p->err);
+        if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
+        return FS_OK;
+    }
     launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_kernel<D>, dim3((unsigned)cw), s,
                   (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
                   sh.num_heads, (int32_t)wgs, sh.trim);
@@ -1550,6 +1608,11 @@ int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
         p->wgs_per_cu = value;
         return FS_OK;
     }
+    if (!std::strcmp(name, "append_in_attention")) {
+        if (value < 0 || value > 1) return FS_ERR_INVALID_ARG;
+        p->append_in_attention = value;
+        return FS_OK;
+    }
     if (!std::strcmp(name, "merge_in_kernel")) {
         if (value < 0 || value > 1) return FS_ERR_INVALID_ARG;
         p->merge_in_kernel = value;
@@ -1565,6 +1628,7 @@ int fs_pool_get_param(const fs_pool *p, const char *name, int32_t *value)
     else if (!std::strcmp(name, "wgs_per_cu")) *value = p->wgs_per_cu;
     else if (!std::strcmp(name, "swap_engine")) *value = p->swap_engine;
     else if (!std::strcmp(name, "merge_in_kernel")) *value = p->merge_in_kernel;
+    else if (!std::strcmp(name, "append_in_attention")) *value = p->append_in_attention;
     else if (!std::strcmp(name, "num_cus")) *value = p->num_cus;
     else if (!std::strcmp(name, "max_jobs_per_launch")) *value = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
     else return FS_ERR_INVALID_ARG;

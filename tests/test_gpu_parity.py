@@ -140,15 +140,17 @@ def test_long_context_full_size_sampled():
 
 
 # ---- fused step: append inside the attention kernel -------------------------------
-@pytest.mark.parametrize("idx,rep", [(0, 0), (0, 1), (1, 0), (2, 1), (3, 2)])
-def test_fused_step_matches_oracle_and_layout(idx, rep):
+@pytest.mark.parametrize("idx,rep,append_in_attention", [(0, 0, 0), (0, 1, 1), (1, 0, 0), (1, 0, 1), (2, 1, 0), (3, 2, 0),
+                                                         (3, 2, 1)])
+def test_fused_step_matches_oracle_and_layout(idx, rep, append_in_attention):
     cfg = wl.CONFIGS[idx]
-    print(f"[case] fused preset {cfg.name} rep {rep}", flush=True)
+    print(f"[case] fused preset {cfg.name} rep {rep} append_in_attention {append_in_attention}", flush=True)
     case = hs.make_case(cfg, rep)
     bt = case.step.tables
     want_img = hs.expected_image(case, bt.table, bt.num_blocks, upto="prefix")
     run = hs.DeviceRun(case, fill="image", prefix_image=want_img)
     try:
+        run.pool.set_param("append_in_attention", append_in_attention)
         got = run.fused_step(max_len_hint=int(case.step.lens.max()))
         run.pool.check()
         img = run.image()
@@ -160,14 +162,18 @@ def test_fused_step_matches_oracle_and_layout(idx, rep):
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128), ("f16", 128), ("f16", 64)])
-def test_fused_step_boundaries(dtype, D):
+@pytest.mark.parametrize("append_in_attention", [0, 1])
+def test_fused_step_boundaries(dtype, D, append_in_attention):
     # lengths after the append; 1 means an empty cache before the step, 65 a cache of
-    # exactly one full 64-token unit, 17 a new token that opens a new block
+    # exactly one full 64-token unit, 17 a new token that opens a new block.
+    # append_in_attention: the new rows are written by the launch after the attention kernel
+    # (0, the default) or by the attention kernel itself (1)
     lens = [1, 2, 16, 17, 64, 65, 66, 128, 129, 1000, 1024, 1025]
     cfg = wl.CONFIGS[1].scaled(num_jobs=len(lens), num_heads=5, head_dim=D, dtype=dtype, max_len=1040)
     case = hs.make_case(cfg, 1, lens=lens)
     run = hs.DeviceRun(case, fill="image")
     try:
+        run.pool.set_param("append_in_attention", append_in_attention)
         got = run.fused_step()
         run.pool.check()
         img = run.image()
