@@ -858,6 +858,10 @@ __device__ __forceinline__ void append_block(
     const long long jh = idx / nk;
     const int h = (int)(jh % H);
     const int j = (int)(jh / H);
+    // the new vectors are asked for first: they depend on nothing, the destination on two lookups
+    const size_t src = ((size_t)jh * nk + vec) * 16;
+    const u32x4 kv = *(const u32x4 *)(k + src);
+    const u32x4 vv = *(const u32x4 *)(v + src);
     const int pos = lens[j];
     if (pos < 0 || pos / kBlockTokens >= table_stride) {
         if (h == 0 && vec == 0) atomicOr(err, kErrBadLen);
@@ -871,9 +875,6 @@ __device__ __forceinline__ void append_block(
     const int slot = pos % kBlockTokens;
     const size_t chunk = (size_t)kBlockTokens * D * EB;
     char *blk = pool + (size_t)bid * (2 * (size_t)H * chunk);
-    const size_t src = ((size_t)jh * nk + vec) * 16;
-    const u32x4 kv = *(const u32x4 *)(k + src);
-    const u32x4 vv = *(const u32x4 *)(v + src);
     *(u32x4 *)(blk + (size_t)h * chunk + ((size_t)vec * kBlockTokens + slot) * 16) = kv;
     *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
 }
