@@ -372,6 +372,22 @@ def test_more_jobs_than_one_launch_slice():
     hs.assert_parity(got, hs.oracle_step(case), "sliced batch")
 
 
+def test_fused_step_over_several_launch_slices():
+    # every slice runs the attention kernel and the combine + append launch on its own jobs
+    cfg = wl.CONFIGS[2].scaled(num_jobs=20, num_heads=3)
+    case = hs.make_case(cfg, 1)
+    run = hs.DeviceRun(case, max_jobs=8, max_workgroups=3)
+    try:
+        got = run.fused_step()
+        run.pool.check()
+        img = run.image()
+    finally:
+        run.close()
+    want = hs.expected_image(case, case.step.tables.table, case.step.tables.num_blocks)
+    assert np.array_equal(img.view(np.uint8), want.view(np.uint8))
+    hs.assert_parity(got, hs.oracle_step(case), "sliced batch, fused")
+
+
 def test_widest_table_of_the_long_context_preset():
     # W = 2048 table entries per job, one job at the full 32768 tokens, 2 heads
     cfg = wl.CONFIGS[4].scaled(num_jobs=1, num_heads=2)
