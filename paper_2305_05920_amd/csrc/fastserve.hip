@@ -452,6 +452,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         fetch_window(trow, kt, w0, w1);
         store_window(w0, w1);
     }
+    FS_TRACE_STAMP(6);
     // the job after this one: its length and first table window are asked for long
     // before the walk reaches it (registers that only the job change below touches)
     int nj = next_job(j);
@@ -501,6 +502,37 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         return bid;
     };
 
+    // Value loads of one unit: its four blocks, four 1 KiB load instructions each.  Rows past
+    // the job's last block repeat that block, slots past its last token repeat that token
+    // (weight zero either way).  `dead`: there is no such unit (the range's last unit has no
+    // successor); the loads then read the first 4 KiB of the pool, one hot set of lines for
+    // every wave, instead of sitting behind a branch.
+    auto issue_values = [&](int bidv, int jj, int hh, int kk, int LL, int NBB, bool dead) {
+#pragma unroll
+        for (int b = 0; b < kStepBlocks; ++b) {
+            const int bb = __builtin_amdgcn_readlane(bidv, 16 * b);
+            int bi = kStepBlocks * kk + b;
+            bi = bi < NBB ? bi : NBB - 1;
+            if (kFused) bi = bi > 0 ? bi : 0;
+            int left = LL - bi * kBlockTokens;  // valid slots of that block (>= 1 unless the cache is empty)
+            const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + hh) * kChunkBytes + (size_t)vc * 16;
+            // fused, empty cache: nothing of this job is in the pool yet; the loads read the
+            // job's own new value row instead (finite data, weight zero), slot 0 below
+            if (kFused && LL == 0) vp = v_new + ((size_t)jj * H + hh) * kRowBytes + (size_t)vc * 16;
+            if (dead) {
+                vp = pool + (size_t)vc * 16;
+                left = kBlockTokens;
+            }
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                int slot = i * TPI + vt;
+                slot = slot < left ? slot : left - 1;
+                if (kFused) slot = slot > 0 ? slot : 0;
+                vr[b][i] = load_stream(vp + (size_t)slot * kRowBytes);
+            }
+        }
+    };
+
     load_q(j, h);
     int bid = row_block(k);
     {
@@ -508,6 +540,10 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 #pragma unroll
         for (int i = 0; i < NK; ++i) kr[i] = load_stream(kp + i * (kBlockTokens * 16));
     }
+    // (keys first, then values, here as in the loop: the waits count loads in issue order)
+    __builtin_amdgcn_sched_barrier(0);
+    FS_TRACE_STAMP(7);
+    issue_values(bid, j, h, k, L, NB, false);
     // fused append: q, key and value vectors of the new token of the pair being finished
     u32x4 xq = u32x4{0u, 0u, 0u, 0u}, xk = xq, xv = xq;
     int xbid = 0;
@@ -520,7 +556,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     for (long long u = lo; u < hi; ++u) {
         const bool last_of_pair = (k == steps - 1);
         const bool last_of_range = (u + 1 == hi);
-        const int j_cur = j, h_cur = h, k_cur = k, L_cur = L, NB_cur = NB;
+        const int j_cur = j, h_cur = h, L_cur = L;
 
         // ---- scores of this unit's 64 tokens (base 2: scale*log2(e) folded in) ----
         float sc;
@@ -535,6 +571,10 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             }
             const int t = (kStepBlocks * k + r) * kBlockTokens + s;
             sc = t < L ? (d0 + d1) * sh.scale_log2e : -INFINITY;
+            // The scores are wanted here, while the keys' successors are not yet asked for:
+            // without this the compiler sinks the dot products below the bookkeeping branches
+            // and then waits for every load in flight, the next values included.
+            asm volatile("" : "+v"(sc));
         }
 #ifdef FS_TRACE
         if (first_unit) {
@@ -582,26 +622,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         }
         const int bid_next = row_block(k);
 
-        // ---- values of this unit's four blocks ----
-#pragma unroll
-        for (int b = 0; b < kStepBlocks; ++b) {
-            const int bb = __builtin_amdgcn_readlane(bid, 16 * b);
-            int bi = kStepBlocks * k_cur + b;
-            bi = bi < NB_cur ? bi : NB_cur - 1;
-            if (kFused) bi = bi > 0 ? bi : 0;
-            const int left = L_cur - bi * kBlockTokens;  // valid slots of that block (>= 1 unless the cache is empty)
-            const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + h_cur) * kChunkBytes + (size_t)vc * 16;
-            // fused, empty cache: nothing of this job is in the pool yet; the loads read the
-            // job's own new value row instead (finite data, weight zero), slot 0 below
-            if (kFused && L_cur == 0) vp = v_new + ((size_t)j_cur * H + h_cur) * kRowBytes + (size_t)vc * 16;
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                int slot = i * TPI + vt;
-                slot = slot < left ? slot : left - 1;
-                if (kFused) slot = slot > 0 ? slot : 0;
-                vr[b][i] = load_stream(vp + (size_t)slot * kRowBytes);
-            }
-        }
         if (kFused && last_of_pair) {
             // the new token's vectors and the block it goes to: asked for now, used at the pair's end
             const size_t row = ((size_t)j_cur * H + h_cur) * kRowBytes + (size_t)vc * 16;
@@ -623,7 +643,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
 #pragma unroll
             for (int i = 0; i < NK; ++i) kr[i] = load_stream(kp + i * (kBlockTokens * 16));
         }
-        bid = bid_next;
 
         // ---- online softmax; the weights reach the value lanes through LDS ----
         {
@@ -652,6 +671,9 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 axpy16<E>(pv[i], vr[b][i].x, vr[b][i].y, vr[b][i].z, vr[b][i].w, acc);
         }
         wave_lds_sync();
+        // ---- the next unit's values go in flight (its keys already are) ----
+        issue_values(bid_next, j, h, k, L, NB, last_of_range);
+        bid = bid_next;
 
         // ---- end of this wave's share of the (job, head) pair ----
         if (last_of_pair || last_of_range) {
@@ -792,12 +814,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         }
     }
     FS_TRACE_STAMP(5);
-#ifdef FS_TRACE
-    if (lane == 0) {
-        trace_buf[((size_t)blockIdx.x * kWavesPerWg + wave) * 8 + 6] = __builtin_amdgcn_s_getreg(63492);  // HW_ID
-        trace_buf[((size_t)blockIdx.x * kWavesPerWg + wave) * 8 + 7] = __builtin_amdgcn_s_getreg(63508);  // XCC_ID
-    }
-#endif
 }
 
 // ------------------------------------------------------------------------------------
