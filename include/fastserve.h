@@ -193,6 +193,26 @@ int fs_decode_attention(const void *q, fs_pool *pool, const int32_t *block_table
                         int32_t table_stride, const int32_t *job_lens, int32_t num_jobs,
                         int32_t max_len_hint, float *out, void *stream);
 
+/* ---- decode attention for callers that cannot allocate ------------------------------
+ * For callers that must not reach an allocating call: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same operation, arguments and result
+ * (bit for bit) as fs_decode_attention, but the partial results and the step plan live in
+ * a fixed device array that is part of the library image (1 069 312 bytes per GPU, held
+ * until the process ends) instead of the pool's allocated scratch, the launches are plain
+ * ones even while fs_profile_enable is on (no events are created), and the
+ * "merge_in_kernel" knob is ignored (the two-launch form always).  The call allocates and
+ * frees nothing.
+ *   Limits: num_jobs <= 1024 in one call (larger batches are refused with
+ *   FS_ERR_INVALID_ARG, not sliced); head_dim <= 128; the attention grid is at most 256
+ *   workgroups.
+ *   Every call on one GPU shares that GPU's array, whichever pool it names: calls that
+ *   overlap in time on one GPU race, also across pools and streams.  The array keeps the
+ *   last call's contents; the kernels write every cell they later read, so nothing needs
+ *   clearing between calls. */
+int fs_decode_attention_static(const void *q, fs_pool *pool, const int32_t *block_table,
+                               int32_t table_stride, const int32_t *job_lens, int32_t num_jobs,
+                               int32_t max_len_hint, float *out, void *stream);
+
 /* ---- fused decode step (Sections 2.2 and 5: one iteration appends and attends; the
  *      paper's engine fuses operations into fewer kernels) ---------------------------
  * Same result as fs_kv_append(pool, table, stride, job_lens, J, k, v) followed by

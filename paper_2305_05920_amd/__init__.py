@@ -26,7 +26,7 @@ EXPORTS = (
     "fs_pool_create", "fs_pool_destroy", "fs_pool_block_bytes", "fs_pool_device_ptr",
     "fs_pool_write_block", "fs_pool_read_block", "fs_pool_check", "fs_kv_append", "fs_kv_prefill",
     "fs_prefill_attention", "fs_prefill_step",
-    "fs_decode_attention", "fs_decode_step", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
+    "fs_decode_attention", "fs_decode_attention_static", "fs_decode_step", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
     "fs_profile_collect", "fs_pool_set_param", "fs_pool_get_param", "fs_pool_last_plan",
     "fs_stream_read", "fs_stream_copy", "fs_strerror", "fs_version",
 )
@@ -77,6 +77,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_prefill_attention.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, vp]
     lib.fs_prefill_step.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, vp, vp, vp]
     lib.fs_decode_attention.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    lib.fs_decode_attention_static.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp]
     lib.fs_decode_step.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, i32, vp, vp]
     lib.fs_pool_offload.argtypes = [vp, vp, vp, i32, vp]
     lib.fs_pool_upload.argtypes = [vp, vp, vp, i32, vp]
@@ -321,6 +322,22 @@ def fs_decode_attention(q: torch.Tensor, pool: Pool, block_table: torch.Tensor, 
                                       _dev(job_lens, "job_lens", torch.int32), J, int(max_len_hint),
                                       _dev(out, "out", torch.float32), _stream_ptr(stream)),
         "fs_decode_attention")
+
+
+def fs_decode_attention_static(q: torch.Tensor, pool: Pool, block_table: torch.Tensor, job_lens: torch.Tensor,
+                               out: torch.Tensor, max_len_hint: int = 0, stream=None) -> None:
+    """fs_decode_attention on the library's fixed device scratch: allocates nothing; at most 1024 jobs."""
+    J = job_lens.numel()
+    shape = (J, pool.num_heads, pool.head_dim)
+    if block_table.dim() != 2 or block_table.shape[0] != J:
+        raise ValueError("block_table: need [num_jobs][table_stride]")
+    if tuple(q.shape) != shape or tuple(out.shape) != shape:
+        raise ValueError(f"q, out: need shape {shape}")
+    _ok(pool._lib.fs_decode_attention_static(_dev(q, "q", pool.torch_dtype), pool._h,
+                                             _dev(block_table, "block_table", torch.int32), block_table.shape[1],
+                                             _dev(job_lens, "job_lens", torch.int32), J, int(max_len_hint),
+                                             _dev(out, "out", torch.float32), _stream_ptr(stream)),
+        "fs_decode_attention_static")
 
 
 def fs_decode_step(pool: Pool, block_table: torch.Tensor, job_lens: torch.Tensor, k: torch.Tensor,

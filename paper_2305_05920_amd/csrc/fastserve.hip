@@ -30,6 +30,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -1085,6 +1086,22 @@ struct ProfileRecord {
 
 }  // namespace
 
+// Scratch of fs_decode_attention_static: partial results and the step plan of one attention
+// launch on a grid of at most kStaticWorkgroups workgroups, in a device array that exists
+// from program load (nothing is allocated, at any time).  Every GPU holds its own copy at
+// its own address; host code never uses the array's name as a pointer, only the address
+// hipGetSymbolAddress returned for the device in question (static_scratch_for()).
+namespace {
+constexpr int kStaticWorkgroups = 256;
+constexpr int kStaticWaves = kStaticWorkgroups * kWavesPerWg;
+constexpr int kStaticHeadDim = 128;
+constexpr size_t kStaticAccBytes = (size_t)kStaticWaves * 2 * kStaticHeadDim * sizeof(float);
+constexpr size_t kStaticMlBytes = (size_t)kStaticWaves * 2 * 2 * sizeof(float);
+constexpr size_t kStaticPlanBytes = ((kMaxJobsPerLaunch + 2) * sizeof(int32_t) + 255) / 256 * 256;
+constexpr size_t kStaticScratchBytes = kStaticAccBytes + kStaticMlBytes + kStaticPlanBytes;
+}  // namespace
+static __device__ __align__(256) unsigned char fs_static_scratch[kStaticScratchBytes];
+
 struct fs_pool {
     fs_pool_config cfg;
     int device = 0;
@@ -1122,6 +1139,7 @@ struct fs_pool {
     int32_t *plan = nullptr;
     PfItem *pf_items = nullptr;  // work list of the prompt-attention launches: count, then entries
     int32_t *err = nullptr;
+    char *static_scratch = nullptr;  // this device's copy of fs_static_scratch (device address)
 #ifdef FS_TRACE
     unsigned long long *trace = nullptr;
 #endif
@@ -1140,6 +1158,28 @@ bool on_pool_device(const fs_pool *p) {
 }
 
 constexpr int kMaxWgsPerCu = 8;
+
+// Device address of fs_static_scratch on `device`, which must be the current device: asked
+// of the runtime once per device and kept (each GPU has its own copy of the array).
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+char *g_static_ptr[kMaxDevices] = {};
+
+int static_scratch_for(int device, char **out)
+{
+    if (device < 0 || device >= kMaxDevices) return FS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(fs_static_scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return FS_ERR_HIP;
+        }
+        g_static_ptr[device] = (char *)ptr;
+    }
+    *out = g_static_ptr[device];
+    return FS_OK;
+}
 
 int alloc_scratch(fs_pool *p) {
     // two partial slots per wave of the largest grid the knobs allow
@@ -1163,7 +1203,7 @@ int alloc_scratch(fs_pool *p) {
 template <typename... Params, typename... Args>
 void launch_kernel(fs_pool *p, int kind, void (*kernel)(Params...), dim3 grid, hipStream_t s, Args... args)
 {
-    if (p->profiling) {
+    if (p->profiling && kind >= 0) {  // kind < 0: a plain launch, whatever the profiling switch says
         ProfileRecord rec{};
         bool have = false;
         if (!p->spare.empty()) {
@@ -1184,9 +1224,21 @@ void launch_kernel(fs_pool *p, int kind, void (*kernel)(Params...), dim3 grid, h
     hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, s, static_cast<Params>(args)...);
 }
 
+// Where one attention call keeps its partial results and its plan: the pool's own buffers, or
+// the static device array (then: a grid of at most kStaticWorkgroups, the two-launch form,
+// plain launches that record no events).
+struct AttnScratch {
+    float *part_acc;
+    float *part_ml;
+    int32_t *plan;
+    int waves_cap;
+    bool is_static;
+};
+
 template <typename E, int D, bool kFused>
-int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v_new, const int32_t *table,
-                     int32_t stride, const int32_t *lens, int32_t J, int32_t max_len, float *out, hipStream_t s)
+int launch_attention(fs_pool *p, const AttnScratch &sc, const void *q, const void *k_new, const void *v_new,
+                     const int32_t *table, int32_t stride, const int32_t *lens, int32_t J, int32_t max_len,
+                     float *out, hipStream_t s)
 {
     AttnShape sh;
     sh.num_jobs = J;
@@ -1194,7 +1246,7 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     sh.table_stride = stride;
     sh.num_blocks = p->cfg.num_blocks;
     sh.scale_log2e = p->scale * 1.4426950408889634f;
-    sh.merge = p->merge_in_kernel;
+    sh.merge = sc.is_static ? 0 : p->merge_in_kernel;
     // one unit = one 64-token step of one (job, head); no more waves than units can exist
     const long long units_bound = (long long)J * sh.num_heads * ceil_div(max_len, kStepTokens);
     long long wgs = (units_bound + kWavesPerWg - 1) / kWavesPerWg;
@@ -1206,14 +1258,18 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     sh.trim = (p->wgs_per_cu == 0 && !kFused) ? 1 : 0;
     if (wgs > persistent) wgs = persistent;
     if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
+    if (sc.is_static && wgs > kStaticWorkgroups) wgs = kStaticWorkgroups;
     if (wgs < 1) wgs = 1;
-    if (wgs * kWavesPerWg > p->waves_cap) return FS_ERR_INVALID_ARG;
+    if (wgs * kWavesPerWg > sc.waves_cap) return FS_ERR_INVALID_ARG;
     // fs_decode_step: the new tokens' rows are written by the attention kernel itself only
     // where no second launch follows (merge mode) or on request; otherwise by that launch
     const bool write_in_kernel = kFused && (sh.merge || p->append_in_attention);
-    launch_kernel(p, FS_KERNEL_ATTENTION, fs_attn_partition_kernel<E, D, kFused>, dim3((unsigned)wgs), s,
+    // (the static variant creates no events: its launches are never recorded)
+    const int kind_attn = sc.is_static ? -1 : (int)FS_KERNEL_ATTENTION;
+    const int kind_comb = sc.is_static ? -1 : (int)FS_KERNEL_COMBINE;
+    launch_kernel(p, kind_attn, fs_attn_partition_kernel<E, D, kFused>, dim3((unsigned)wgs), s,
                   (const uint32_t *)q, (const char *)p->mem, write_in_kernel ? p->mem : (char *)nullptr,
-                  (const char *)k_new, (const char *)v_new, table, lens, out, p->part_acc, p->part_ml, p->plan,
+                  (const char *)k_new, (const char *)v_new, table, lens, out, sc.part_acc, sc.part_ml, sc.plan,
                   p->err, p->pair_cnt, sh
 #ifdef FS_TRACE
                   , p->trace
@@ -1225,15 +1281,15 @@ int launch_attention(fs_pool *p, const void *q, const void *k_new, const void *v
     if (kFused && !write_in_kernel) {
         const long long vecs = (long long)J * sh.num_heads * (D * E::kBytes / 16);
         const long long aw = (vecs + kThreads - 1) / kThreads;
-        launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_append_kernel<D, E::kBytes>, dim3((unsigned)(cw + aw)), s,
-                      (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
+        launch_kernel(p, kind_comb, fs_attn_combine_append_kernel<D, E::kBytes>, dim3((unsigned)(cw + aw)), s,
+                      (const float *)sc.part_acc, (const float *)sc.part_ml, (const int32_t *)sc.plan, out, J,
                       sh.num_heads, (int32_t)wgs, sh.trim, (int32_t)cw, p->mem, table, stride, lens,
                       sh.num_blocks, (const char *)k_new, (const char *)v_new, p->err);
         if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
         return FS_OK;
     }
-    launch_kernel(p, FS_KERNEL_COMBINE, fs_attn_combine_kernel<D>, dim3((unsigned)cw), s,
-                  (const float *)p->part_acc, (const float *)p->part_ml, (const int32_t *)p->plan, out, J,
+    launch_kernel(p, kind_comb, fs_attn_combine_kernel<D>, dim3((unsigned)cw), s,
+                  (const float *)sc.part_acc, (const float *)sc.part_ml, (const int32_t *)sc.plan, out, J,
                   sh.num_heads, (int32_t)wgs, sh.trim);
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     return FS_OK;
@@ -1268,6 +1324,12 @@ int fs_pool_create(const fs_pool_config *cfg, fs_pool **out)
     }
     p->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     p->max_workgroups = cfg->max_workgroups;
+    // set-up of fs_decode_attention_static: this device's address of the static scratch
+    // array, looked up once per device while that device is current
+    if (static_scratch_for(p->device, &p->static_scratch) != FS_OK) {
+        delete p;
+        return FS_ERR_HIP;
+    }
     const size_t need = p->block_bytes * (size_t)cfg->num_blocks;
     if (cfg->device_mem) {
         if (cfg->device_bytes < need || ((uintptr_t)cfg->device_mem & 255u)) {
@@ -1474,11 +1536,21 @@ int fs_prefill_step(fs_pool *p, const int32_t *table, int32_t stride, const int3
     return run_prefill_attention(p, true, table, stride, q, k, v, offs, J, total_tokens, out, stream);
 }
 
-static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_new, const void *v_new,
-                         const int32_t *table, int32_t stride, const int32_t *lens, int32_t J,
+static int run_attention(fs_pool *p, bool fused, bool use_static, const void *q, const void *k_new,
+                         const void *v_new, const int32_t *table, int32_t stride, const int32_t *lens, int32_t J,
                          int32_t max_len_hint, float *out, void *stream)
 {
     if (!p || J < 0) return FS_ERR_INVALID_ARG;
+    AttnScratch sc{p->part_acc, p->part_ml, p->plan, p->waves_cap, false};
+    if (use_static) {
+        // beyond the static array's capacity: refused, never served in part
+        if (J > kMaxJobsPerLaunch || p->cfg.head_dim > kStaticHeadDim || !p->static_scratch) return FS_ERR_INVALID_ARG;
+        sc.part_acc = (float *)p->static_scratch;
+        sc.part_ml = (float *)(p->static_scratch + kStaticAccBytes);
+        sc.plan = (int32_t *)(p->static_scratch + kStaticAccBytes + kStaticMlBytes);
+        sc.waves_cap = kStaticWaves;
+        sc.is_static = true;
+    }
     if (J == 0) return FS_OK;
     if (!q || !table || !lens || !out || stride <= 0) return FS_ERR_INVALID_ARG;
     if (fused && (!k_new || !v_new)) return FS_ERR_INVALID_ARG;
@@ -1488,7 +1560,7 @@ static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_ne
     const int H = p->cfg.num_heads, D = p->cfg.head_dim;
     int max_len = stride * kBlockTokens;
     if (max_len_hint > 0 && max_len_hint < max_len) max_len = max_len_hint;
-    const int slice = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
+    const int slice = use_static ? kMaxJobsPerLaunch : (p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch);
     const size_t row_bytes = (size_t)H * D * p->elem_bytes;
     for (int j0 = 0; j0 < J; j0 += slice) {
         const int n = (J - j0) < slice ? (J - j0) : slice;
@@ -1500,8 +1572,8 @@ static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_ne
         float *os = out + (size_t)j0 * H * D;
         int rc;
 #define FS_LAUNCH(E, DD)                                                                                 \
-    (fused ? launch_attention<E, DD, true>(p, qs, ks, vs, ts, stride, ls, n, max_len, os, s)              \
-           : launch_attention<E, DD, false>(p, qs, ks, vs, ts, stride, ls, n, max_len, os, s))
+    (fused ? launch_attention<E, DD, true>(p, sc, qs, ks, vs, ts, stride, ls, n, max_len, os, s)          \
+           : launch_attention<E, DD, false>(p, sc, qs, ks, vs, ts, stride, ls, n, max_len, os, s))
         if (p->cfg.dtype == FS_BF16)
             rc = D == 128 ? FS_LAUNCH(BF16, 128) : FS_LAUNCH(BF16, 64);
         else if (p->cfg.dtype == FS_F16)
@@ -1517,13 +1589,19 @@ static int run_attention(fs_pool *p, bool fused, const void *q, const void *k_ne
 int fs_decode_attention(const void *q, fs_pool *p, const int32_t *table, int32_t stride,
                         const int32_t *lens, int32_t J, int32_t max_len_hint, float *out, void *stream)
 {
-    return run_attention(p, false, q, nullptr, nullptr, table, stride, lens, J, max_len_hint, out, stream);
+    return run_attention(p, false, false, q, nullptr, nullptr, table, stride, lens, J, max_len_hint, out, stream);
+}
+
+int fs_decode_attention_static(const void *q, fs_pool *p, const int32_t *table, int32_t stride,
+                               const int32_t *lens, int32_t J, int32_t max_len_hint, float *out, void *stream)
+{
+    return run_attention(p, false, true, q, nullptr, nullptr, table, stride, lens, J, max_len_hint, out, stream);
 }
 
 int fs_decode_step(fs_pool *p, const int32_t *table, int32_t stride, const int32_t *lens, int32_t J,
                    const void *k, const void *v, const void *q, int32_t max_len_hint, float *out, void *stream)
 {
-    return run_attention(p, true, q, k, v, table, stride, lens, J, max_len_hint, out, stream);
+    return run_attention(p, true, false, q, k, v, table, stride, lens, J, max_len_hint, out, stream);
 }
 
 static int copy_blocks(fs_pool *p, const int32_t *block_ids, const int32_t *host_slots, int32_t n, void *stream,
