@@ -8,7 +8,8 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "fastserve.hip"), os.path.join(HERE, "csrc", "serving.cpp")]
+SOURCES = [os.path.join(HERE, "csrc", "fastserve.hip"), os.path.join(HERE, "csrc", "serving.cpp"),
+           os.path.join(HERE, "csrc", "kvm.cpp")]
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(HERE, "libfastserve.so")
 

@@ -47,16 +47,20 @@ def _ids(seq: Sequence[int]):
 
 
 class Scheduler:
-    def __init__(self, num_queues: int, q1: float, eta: int, alpha: float, max_batch: int):
+    def __init__(self, num_queues: int, q1: float, eta: int, alpha: float, max_batch: int, _handle=None):
         self._lib = _lib()
+        self._owned = _handle is None
+        if _handle is not None:                     # a scheduler some other object of the library owns
+            self._h, self.max_batch = ctypes.c_void_p(_handle), max_batch
+            return
         h = ctypes.c_void_p()
         _ok(self._lib.fs_sched_create(num_queues, q1, eta, alpha, max_batch, ctypes.byref(h)), "fs_sched_create")
         self._h, self.max_batch = h, max_batch
 
     def close(self) -> None:
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and self._owned:
             self._lib.fs_sched_destroy(self._h)
-            self._h = None
+        self._h = None
 
     def __del__(self):
         try:

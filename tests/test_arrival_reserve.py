@@ -1,54 +1,62 @@
 """The idle-block reserve that follows the arrival history (paper Section 4.2, "Handling a burst
 of new jobs"; the estimator is this build's reading: a high quantile of the per-iteration demand
-over a sliding window).  Host logic only."""
+over a sliding window), asked of the library's cache manager through its C ABI.  Host logic only."""
+import os
+
 import pytest
 
-from paper_2305_05920_amd.kv_manager import ArrivalReserve
+
+@pytest.fixture(scope="module")
+def kvm():
+    import paper_2305_05920_amd as fs
+    if not os.path.exists(fs.LIB_PATH):
+        from paper_2305_05920_amd import build
+        build.build_library()
+    from paper_2305_05920_amd import kvm
+    return kvm
 
 
-def load_reserve_class():
-    return ArrivalReserve
+def reserve_after(kvm, demands, window, quantile, floor=0, blocks=400):
+    k = kvm.KVManager(None, None, blocks, 0, 4, reserve_idle_blocks=floor, reserve_window=window,
+                      reserve_quantile=quantile)
+    try:
+        for d in demands:
+            k.observe_arrivals(d)
+        return k.reserve
+    finally:
+        k.close()
 
 
-def test_no_history_gives_the_floor():
-    R = load_reserve_class()
-    assert R(floor=3).blocks() == 3 and R().blocks() == 0
+def test_no_history_gives_the_floor(kvm):
+    assert reserve_after(kvm, [], 8, 0.9, floor=3) == 3 and reserve_after(kvm, [], 8, 0.9) == 0
 
 
-def test_quiet_traffic_reserves_little_and_bursts_reserve_more():
-    R = load_reserve_class()
-    quiet, bursty = R(window=50, quantile=0.9), R(window=50, quantile=0.9)
-    for i in range(50):
-        quiet.observe(2 if i % 10 == 0 else 0)           # a small job now and then
-        bursty.observe(40 if i % 5 == 0 else 0)           # a burst of new jobs every fifth iteration
-    assert quiet.blocks() <= 2
-    assert bursty.blocks() == 40
-    assert bursty.blocks() > quiet.blocks()
+def test_quiet_traffic_reserves_little_and_bursts_reserve_more(kvm):
+    quiet = [2 if i % 10 == 0 else 0 for i in range(50)]             # a small job now and then
+    bursty = [40 if i % 5 == 0 else 0 for i in range(50)]            # a burst of new jobs every fifth iteration
+    assert reserve_after(kvm, quiet, 50, 0.9) <= 2
+    assert reserve_after(kvm, bursty, 50, 0.9) == 40
 
 
-def test_more_frequent_bursts_never_reserve_less():
-    R = load_reserve_class()
+def test_more_frequent_bursts_never_reserve_less(kvm):
     last = -1
-    for period in (40, 20, 10, 5, 2):                      # bursts of 30 blocks, ever more frequent
-        r = R(window=40, quantile=0.9)
-        for i in range(40):
-            r.observe(30 if i % period == 0 else 0)
-        assert r.blocks() >= last
-        last = r.blocks()
+    for period in (40, 20, 10, 5, 2):                                 # bursts of 30 blocks, ever more frequent
+        r = reserve_after(kvm, [30 if i % period == 0 else 0 for i in range(40)], 40, 0.9)
+        assert r >= last
+        last = r
     assert last == 30
 
 
-def test_old_bursts_are_forgotten_and_the_floor_holds():
-    R = load_reserve_class()
-    r = R(window=8, quantile=1.0, floor=1)
-    r.observe(100)
-    for _ in range(8):
-        r.observe(0)
-    assert r.blocks() == 1
+def test_old_bursts_are_forgotten_and_the_floor_holds(kvm):
+    assert reserve_after(kvm, [100] + [0] * 8, 8, 1.0, floor=1) == 1
 
 
-def test_bad_parameters_are_refused():
-    R = load_reserve_class()
-    for kw in ({"window": 0}, {"quantile": 1.5}, {"floor": -1}):
-        with pytest.raises(ValueError):
-            R(**kw)
+def test_the_reserve_never_takes_more_than_half_the_pool(kvm):
+    assert reserve_after(kvm, [500], 4, 1.0, blocks=100) == 50
+
+
+def test_bad_parameters_are_refused(kvm):
+    import paper_2305_05920_amd as fs
+    for kw in ({"reserve_window": -1}, {"reserve_quantile": 1.5}, {"reserve_idle_blocks": -1}):
+        with pytest.raises(fs.FsError):
+            kvm.KVManager(None, None, 8, 0, 4, **kw)

@@ -85,20 +85,24 @@ def test_long_context_reduced_job_count(rep):
     hs.assert_parity(got, hs.oracle_step(case), f"long_context reduced rep {rep}")
 
 
-def test_long_context_full_size_sampled():
+@pytest.mark.parametrize("rep", [0, 1, 2])
+def test_long_context_full_size_every_row(rep):
     # preset 4 at its full size (8 jobs of 16k-32k tokens, 64 heads: ~6 GB of KV) in the
-    # launch configuration bench.py times.  The oracle recomputes sampled (job, head)
-    # rows one by one; every other row must be finite and inside the convex hull bound
-    # that holds for any attention output (|out| <= max |v| over the job's cache).
+    # launch configuration bench.py times; every one of the 8 x 64 x 128 outputs is compared
+    # with the oracle (one oracle call per job, the jobs on separate host threads).  Seed 0
+    # also runs the fused step on the same pool: it rewrites the appended rows with the same
+    # bits and must agree with the oracle as well.
+    from concurrent.futures import ThreadPoolExecutor
     import paper_2305_05920_amd as fs
     cfg = wl.CONFIGS[4]
-    print("[case] preset long_context full size", flush=True)
-    case = hs.make_case(cfg, 0)
+    print(f"[case] preset long_context full size rep {rep}", flush=True)
+    case = hs.make_case(cfg, rep)
     bt = case.step.tables
     H, D = cfg.num_heads, cfg.head_dim
     lay = hs.layout_of(cfg)
     mem = torch.empty((bt.num_blocks, lay.block_elems), dtype=torch.bfloat16, device="cuda")
     table = torch.from_numpy(bt.table).cuda()
+    lens_max = int(case.step.lens.max())
     with fs.Pool(cfg.dtype, H, D, bt.num_blocks, device_mem=mem) as pool:
         for j, (K, V) in enumerate(case.caches):          # bulk write job by job
             n = int(case.lens_before[j])
@@ -106,16 +110,21 @@ def test_long_context_full_size_sampled():
                              torch.tensor([0, n], dtype=torch.int32, device="cuda"), n,
                              hs.to_torch(cfg.dtype, K[:n]), hs.to_torch(cfg.dtype, V[:n]))
             torch.cuda.synchronize()
-        fs.fs_kv_append(pool, table, torch.from_numpy(case.lens_before).cuda(),
-                        hs.to_torch(cfg.dtype, case.k_new), hs.to_torch(cfg.dtype, case.v_new))
+        d_before = torch.from_numpy(case.lens_before).cuda()
+        d_k, d_v, d_q = (hs.to_torch(cfg.dtype, a) for a in (case.k_new, case.v_new, case.step.q))
+        fs.fs_kv_append(pool, table, d_before, d_k, d_v)
         out = torch.full((cfg.num_jobs, H, D), float("nan"), dtype=torch.float32, device="cuda")
-        fs.fs_decode_attention(hs.to_torch(cfg.dtype, case.step.q), pool, table,
-                               torch.from_numpy(case.step.lens).cuda(), out,
-                               max_len_hint=int(case.step.lens.max()))
+        fs.fs_decode_attention(d_q, pool, table, torch.from_numpy(case.step.lens).cuda(), out, max_len_hint=lens_max)
         pool.check()
         got = out.cpu().numpy()
+        got_fused = None
+        if rep == 0:
+            out.fill_(float("nan"))
+            fs.fs_decode_step(pool, table, d_before, d_k, d_v, d_q, out, max_len_hint=lens_max)
+            pool.check()
+            got_fused = out.cpu().numpy()
         # placement: sampled blocks read back through the C ABI against the layout model
-        rng = np.random.default_rng(4)
+        rng = np.random.default_rng(4 + rep)
         for j in rng.choice(cfg.num_jobs, size=3, replace=False):
             K, V = case.caches[j]
             for bi in (0, int(case.step.lens[j] - 1) // 16, int(rng.integers(0, case.step.lens[j] // 16))):
@@ -123,20 +132,13 @@ def test_long_context_full_size_sampled():
                 n = min(16, int(case.step.lens[j]) - bi * 16)
                 k1, v1 = lay.read_tokens(blk, np.zeros(1, dtype=np.int32), 0, n)
                 assert np.array_equal(k1, K[bi * 16:bi * 16 + n]) and np.array_equal(v1, V[bi * 16:bi * 16 + n])
-    assert np.isfinite(got).all()
-    for j, (K, V) in enumerate(case.caches):
-        vmax = wl.bf16_bits_to_f32(V).__abs__().max(axis=0)            # [H][D]
-        assert (np.abs(got[j]) <= vmax + 1e-6).all()
-    worst = 0.0
-    for _ in range(24):
-        j, h = int(rng.integers(cfg.num_jobs)), int(rng.integers(H))
-        K, V = case.caches[j]
-        ref = oracle.attention_job(case.step.q[j], K, V, cfg.dtype, heads=(h, h + 1))[h]
-        err = np.abs(got[j, h] - ref).max()
-        rel = np.linalg.norm(got[j, h] - ref) / np.linalg.norm(ref)
-        worst = max(worst, err)
-        assert err <= hs.MAX_ABS_TOL and rel <= hs.REL_L2_TOL, (j, h, err, rel)
-    print(f"[parity] long_context full size: worst sampled max_abs={worst:.3e}", flush=True)
+    # the caches' last rows are the appended tokens: attention over the whole logical cache
+    with ThreadPoolExecutor(max_workers=cfg.num_jobs) as ex:
+        ref = np.stack(list(ex.map(lambda j: oracle.attention_job(case.step.q[j], *case.caches[j], cfg.dtype),
+                                   range(cfg.num_jobs))))
+    hs.assert_parity(got, ref, f"long_context full size rep {rep}, all {got.size} outputs")
+    if got_fused is not None:
+        hs.assert_parity(got_fused, ref, f"long_context full size rep {rep}, fused step")
 
 
 # ---- fused step: append inside the attention kernel -------------------------------

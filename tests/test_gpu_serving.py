@@ -19,125 +19,145 @@ pytestmark = pytest.mark.gpu
 
 def test_serving_loop_with_preemption_and_swapping_matches_oracle():
     import paper_2305_05920_amd as fs
-    from paper_2305_05920_amd.kv_manager import ArrivalReserve, KVManager
-    from paper_2305_05920_amd.sched import Scheduler
+    from paper_2305_05920_amd.kvm import ServeLoop
 
     H, D, W = 4, 128, 16                       # up to 256 tokens per job
-    cfg = wl.CONFIGS[1].scaled(num_heads=H, head_dim=D)
     rng = np.random.default_rng(2305)
-    njobs = 16
+    njobs, max_batch = 16, 4
     prompts = rng.integers(20, 150, size=njobs)
     outputs = rng.integers(3, 12, size=njobs)
     arrival = np.sort(rng.integers(0, 12, size=njobs))
     # HBM pool of 36 blocks (576 tokens) for ~1800 tokens of live cache: swapping is forced
     NL = 2                                     # two layers: one pool each, one table for both
     pools = [fs.Pool("bf16", H, D, 36, num_host_blocks=160) for _ in range(NL)]
-    pool = pools[0]
-    sched = Scheduler(4, 1.0, 1, 6.0, 4)
-    kv = KVManager(pools, sched, W, reserve_idle_blocks=4)
-    kv.arrival_reserve = ArrivalReserve(window=8, quantile=0.75, floor=4)   # the reserve follows the arrivals
+    # scheduler, cache manager (reserve following the arrivals) and the loop itself are the library's
+    loop = ServeLoop(pools, 4, 1.0, 1, 6.0, max_batch, 36, 160, W, max_prompt_tokens=600, reserve_idle_blocks=4,
+                     reserve_window=8, reserve_quantile=0.75)
+    for j in range(njobs):
+        loop.submit(j, int(arrival[j]), int(prompts[j]), int(outputs[j]), float(prompts[j]) / 32.0, 1.0)
 
     def rand_bits(shape):
         return wl.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))
+
+    def dev(shape):
+        return torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+
+    pq, pk, pv = dev((600, H, D)), dev((600, H, D)), dev((600, H, D))
+    dq, dk, dv = dev((max_batch, H, D)), dev((max_batch, H, D)), dev((max_batch, H, D))
+    pout = torch.zeros((600, H, D), dtype=torch.float32, device="cuda")
+    dout = torch.zeros((max_batch, H, D), dtype=torch.float32, device="cuda")
+    bufs = ServeLoop.buffers(pq, pk, pv, pout, dq, dk, dv, dout)
 
     # logical caches (oracle side), one per layer and job
     K = {(l, j): np.zeros((256, H, D), np.uint16) for l in range(NL) for j in range(njobs)}
     V = {(l, j): np.zeros((256, H, D), np.uint16) for l in range(NL) for j in range(njobs)}
     length = {j: 0 for j in range(njobs)}
-    produced = {j: 0 for j in range(njobs)}
-    waiting, done = [], set()
     last_ran, preempted = {}, set()
-    checked = 0
-    prompt_rows = 0
-    it = 0
-    while len(done) < njobs:
+    checked = prompt_rows = it = 0
+    while True:
         assert it < 600, "serving loop does not terminate"
-        new = [j for j in range(njobs) if arrival[j] == it]
-        kv.observe_arrivals(sum(kv.blocks_needed(int(prompts[j]) + 1) for j in new))
-        waiting += new
-        for j in list(waiting):                                  # admission: prompt must fit beside the reserve
-            if kv.blocks_needed(int(prompts[j]) + 1) + kv.reserve <= len(kv.free_blocks):
-                kv.admit(j, int(prompts[j]) + 1)
-                sched.add_job(j, float(prompts[j]) / 32.0, 1.0)
-                waiting.remove(j)
-        batch = [j for j in sched.schedule()]
-        # a decoding job needs room for one more token; if HBM is full it sits this one out
-        runnable = [j for j in batch if length[j] == 0 or kv.grow(j, 1)]
-        kv.start_swaps(runnable, want_free=len(batch) - len(runnable) + len(waiting))
-        first = [j for j in runnable if length[j] == 0]
-        decode = [j for j in runnable if length[j] > 0]
-        if first:                                                # initialization phase, all new jobs in one launch per layer
-            ns = [int(prompts[j]) for j in first]
-            offs = np.zeros(len(first) + 1, dtype=np.int32)
-            offs[1:] = np.cumsum(ns)
-            d_table, d_offs = torch.from_numpy(kv.table_rows(first)).cuda(), torch.from_numpy(offs).cuda()
-            for l in range(NL):
-                pq, pk, pv = (rand_bits((int(offs[-1]), H, D)) for _ in range(3))
-                pout = torch.full((int(offs[-1]), H, D), float("nan"), dtype=torch.float32, device="cuda")
-                fs.fs_prefill_step(pools[l], d_table, d_offs, hs.to_torch("bf16", pk), hs.to_torch("bf16", pv),
-                                   hs.to_torch("bf16", pq), pout)
-                torch.cuda.synchronize()
+        plan = loop.plan()
+        if plan["n_unfinished"] == 0:
+            loop.complete()
+            break
+        first, decode, offs = plan["first"], plan["decode"], plan["token_offsets"]
+        assert plan["lens_before"] == [length[j] for j in decode]
+        for l in range(NL):                                      # a model: one launch per layer, its own projections
+            T = plan["prompt_tokens"]
+            if first:
+                hq, hk, hv = (rand_bits((T, H, D)) for _ in range(3))
+                pq[:T].copy_(hs.to_torch("bf16", hq)), pk[:T].copy_(hs.to_torch("bf16", hk))
+                pv[:T].copy_(hs.to_torch("bf16", hv))
+                pout.fill_(float("nan"))
+            if decode:
+                n = len(decode)
+                q, kn, vn = (rand_bits((n, H, D)) for _ in range(3))
+                dq[:n].copy_(hs.to_torch("bf16", q)), dk[:n].copy_(hs.to_torch("bf16", kn))
+                dv[:n].copy_(hs.to_torch("bf16", vn))
+                dout.fill_(float("nan"))
+            if first or decode:
+                loop.launch(bufs, layer=l)
+            torch.cuda.synchronize()
+            pools[l].check()
+            if first:
                 pgot = pout.cpu().numpy()
                 for r, j in enumerate(first):
-                    a, b = int(offs[r]), int(offs[r + 1])
-                    K[l, j][:ns[r]], V[l, j][:ns[r]] = pk[a:b], pv[a:b]
-                    ref = oracle.prefill_attention_job(np.ascontiguousarray(pq[a:b]), np.ascontiguousarray(pk[a:b]),
-                                                       np.ascontiguousarray(pv[a:b]), "bf16")
-                    hs.assert_parity(pgot[a:b], ref, f"iteration {it} layer {l} prompt of job {j} ({ns[r]} tokens)")
-                    prompt_rows += ns[r]
-            for r, j in enumerate(first):
-                kv.advance(j, ns[r])
-                length[j] = ns[r]
-        layer_out = []
-        if decode:                                               # decoding phase: one fused step per layer
-            lens_before = np.array([length[j] for j in decode], dtype=np.int32)
-            d_table, d_lens = torch.from_numpy(kv.table_rows(decode)).cuda(), torch.from_numpy(lens_before).cuda()
-            for l in range(NL):
-                q, kn, vn = (rand_bits((len(decode), H, D)) for _ in range(3))
-                out = torch.full((len(decode), H, D), float("nan"), dtype=torch.float32, device="cuda")
-                fs.fs_decode_step(pools[l], d_table, d_lens, hs.to_torch("bf16", kn), hs.to_torch("bf16", vn),
-                                  hs.to_torch("bf16", q), out)
-                layer_out.append((q, kn, vn, out))
-        kv.finish_swaps()
-        torch.cuda.synchronize()
-        for p in pools:
-            p.check()
-        if decode:
-            for l, (q, kn, vn, out) in enumerate(layer_out):
-                got = out.cpu().numpy()
+                    a, b = offs[r], offs[r + 1]
+                    assert b - a == prompts[j]
+                    K[l, j][:b - a], V[l, j][:b - a] = hk[a:b], hv[a:b]
+                    ref = oracle.prefill_attention_job(np.ascontiguousarray(hq[a:b]), np.ascontiguousarray(hk[a:b]),
+                                                       np.ascontiguousarray(hv[a:b]), "bf16")
+                    hs.assert_parity(pgot[a:b], ref, f"iteration {it} layer {l} prompt of job {j} ({b - a} tokens)")
+                    prompt_rows += b - a
+            if decode:
+                got = dout.cpu().numpy()
                 for r, j in enumerate(decode):
                     K[l, j][length[j]], V[l, j][length[j]] = kn[r], vn[r]
                     ref = oracle.attention_job(q[r], K[l, j], V[l, j], "bf16", length=length[j] + 1)
                     err = np.abs(got[r] - ref).max()
-                    assert err <= hs.MAX_ABS_TOL, (it, l, j, err)
+                    rel = np.linalg.norm(got[r] - ref) / np.linalg.norm(ref)
+                    assert err <= hs.MAX_ABS_TOL and rel <= hs.REL_L2_TOL, (it, l, j, err, rel)
                     checked += 1
-            for j in decode:
-                length[j] += 1
-                kv.advance(j, 1)
-        finished = []
-        for j in runnable:
-            produced[j] += 1
+        for j in first:
+            length[j] = int(prompts[j])
+        for j in decode:
+            length[j] += 1
+        for j in first + decode:
             if j in last_ran and last_ran[j] < it - 1:
                 preempted.add(j)                                  # it waited while others ran
             last_ran[j] = it
-            if produced[j] == outputs[j]:
-                finished.append(j)
-        elapsed = max([float(prompts[j]) / 32.0 if j in first else 1.0 for j in runnable], default=1.0)
-        sched.complete_iteration(runnable, elapsed, finished)
-        for j in finished:
-            kv.release(j)
-            done.add(j)
+        loop.complete()
         it += 1
+    st = loop.stats()
+    loop.manager.retire(wait=True)
     print(f"[serving] {it} iterations, {prompt_rows} prompt rows and {checked} decode outputs checked, "
-          f"{len(preempted)} jobs preempted, "
-          f"{kv.swapped_out_blocks} blocks swapped out, {kv.swapped_in_blocks} swapped in", flush=True)
+          f"{len(preempted)} jobs preempted, {st['blocks_swapped_out']} blocks swapped out, "
+          f"{st['blocks_swapped_in']} swapped in", flush=True)
+    assert st["finished_jobs"] == njobs and st["job_tokens"] == int(outputs.sum())
     assert checked == NL * int((outputs - 1).sum()) and prompt_rows == NL * int(prompts.sum())
-    assert kv.swapped_out_blocks > 0 and kv.swapped_in_blocks > 0, "the test did not exercise swapping"
+    assert st["blocks_swapped_out"] > 0 and st["blocks_swapped_in"] > 0, "the test did not exercise swapping"
     assert preempted, "no job was ever preempted"
-    assert len(kv.free_blocks) == pool.num_blocks and len(kv.free_slots) == pool.num_host_blocks
-    sched.close()
+    assert loop.manager.free_blocks == 36 and loop.manager.free_slots == 160
+    loop.close()
     for p in pools:
         p.close()
+
+
+def test_compiled_loop_runs_a_trace_to_completion_without_host_waits():
+    # fs_serve_run: the whole multi-iteration run inside the library (no Python between iterations);
+    # afterwards every job has finished, every block and slot is back, no kernel met a bad table
+    import paper_2305_05920_amd as fs
+    from paper_2305_05920_amd.kvm import ServeLoop
+    H, D, W, max_batch = 8, 128, 24, 8
+    rng = np.random.default_rng(77)
+    njobs = 48
+    prompts = np.clip(np.round(rng.exponential(96.0, njobs)), 8, 300).astype(int)
+    outputs = np.clip(np.floor(rng.pareto(1.2, njobs) * 8 + 2), 2, 64).astype(int)
+    arrival = np.sort(rng.integers(0, 40, size=njobs))
+    nblocks = 96                                                   # ~1500 tokens of HBM for ~8000 tokens of live cache
+    pool = fs.Pool("bf16", H, D, nblocks, num_host_blocks=1200)
+    loop = ServeLoop([pool], 6, 1.0, 1, 30.0, max_batch, nblocks, 1200, W, max_prompt_tokens=1024,
+                     reserve_idle_blocks=8)
+    for j in range(njobs):
+        loop.submit(j, int(arrival[j]), int(prompts[j]), int(outputs[j]), float(prompts[j]) / 64.0, 1.0)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    pq, pk, pv = (torch.randn((1024, H, D), generator=g, device="cuda").to(torch.bfloat16) for _ in range(3))
+    dq, dk, dv = (torch.randn((max_batch, H, D), generator=g, device="cuda").to(torch.bfloat16) for _ in range(3))
+    pout = torch.full((1024, H, D), float("nan"), dtype=torch.float32, device="cuda")
+    dout = torch.full((max_batch, H, D), float("nan"), dtype=torch.float32, device="cuda")
+    st = loop.run(ServeLoop.buffers(pq, pk, pv, pout, dq, dk, dv, dout), 20000)
+    torch.cuda.synchronize()
+    pool.check()
+    loop.manager.retire(wait=True)
+    print(f"[serving] compiled loop: {st}", flush=True)
+    assert st["finished_jobs"] == njobs and st["job_tokens"] == int(outputs.sum())
+    assert st["prompt_tokens"] == int(prompts.sum())
+    assert st["blocks_swapped_out"] > 0 and st["blocks_swapped_in"] > 0
+    assert loop.manager.free_blocks == nblocks and loop.manager.free_slots == 1200
+    assert torch.isfinite(dout[:1]).all()
+    loop.close()
+    pool.close()
 
 
 def test_iteration_time_profile_feeds_skip_join():
