@@ -42,8 +42,6 @@ def algorithmic_bytes(cfg, lens) -> int:
 class Replicas:
     """R copies of one workload's pool in HBM, each behind its own fs_pool."""
 
-    SWAP_BLOCKS = 8   # most blocks moved each way per step in the swap-overlap measurement
-
     def __init__(self, fs, torch, wl, cfg, rep, min_footprint_bytes, pool_kw, log):
         self.fs, self.torch, self.cfg = fs, torch, cfg
         step = wl.make_step(cfg, rep)
@@ -57,13 +55,8 @@ class Replicas:
         R = min(R, max(2, int(24e9 // pool_bytes)))
         self.R = R
         tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[cfg.dtype]
-        # SWAP_BLOCKS extra blocks at the end of each pool: a waiting job's blocks that
-        # travel to the host and back while the batch runs (swap-overlap measurement)
-        nb_all = bt.num_blocks + self.SWAP_BLOCKS
-        self.mem = torch.empty((R, nb_all, block_elems), dtype=tdt, device="cuda")
-        self.pools = [fs.Pool(cfg.dtype, H, D, nb_all, device_mem=self.mem[r],
-                              num_host_blocks=self.SWAP_BLOCKS, **pool_kw) for r in range(R)]
-        self.spare_blocks = np.arange(bt.num_blocks, nb_all, dtype=np.int32)
+        self.mem = torch.empty((R, bt.num_blocks, block_elems), dtype=tdt, device="cuda")
+        self.pools = [fs.Pool(cfg.dtype, H, D, bt.num_blocks, device_mem=self.mem[r], **pool_kw) for r in range(R)]
         self.table = torch.from_numpy(bt.table).cuda()
         self.lens = torch.from_numpy(step.lens).cuda()
         lens_before = (step.lens - 1).astype(np.int32)
@@ -126,63 +119,131 @@ class Replicas:
             p.close()
 
 
-def swap_overlap(torch, reps, steps, warmup):
-    """Steps with block traffic to and from pinned host memory on a side stream (the
-    paper's proactive swapping, Section 4.2): every step, SWAP_BLOCKS blocks that no
-    running job uses leave for host slots and come back."""
-    fs = reps.fs
-    block_bytes = reps.pools[0].block_bytes
-    # traffic sized to about 12 GB/s each way at the step's expected duration, i.e. well
-    # inside what the host link sustains (measured here: ~37 GB/s both ways together)
-    est_step_s = reps.alg_bytes / 5.5e12 + 15e-6
-    n = int(min(len(reps.spare_blocks), max(1, 12e9 * est_step_s // block_bytes)))
-    ids = reps.spare_blocks[:n]
-    slots = np.arange(len(ids), dtype=np.int32)
-    side = torch.cuda.Stream()
+def swap_overlap(fs, torch, wl, cfg, log, steps=150, warmup=20, waiting_jobs=48, waiting_tokens=1024):
+    """Decode steps of the preset's batch while the cache manager (C++, fs_kvm_*) swaps WAITING jobs
+    between HBM and pinned host memory on its side stream, in the order of their estimated next
+    scheduled time (paper Section 4.2): every other step it is asked for `rate` more free blocks
+    (jobs leave), in between for none (jobs return).  The rate is swept from nothing to more than
+    the host link carries; copies that do not finish within a step simply stay in flight (their
+    events are polled).  Reported per rate: the step time, the attention kernel's own duration
+    and the bytes that crossed the link per second of the timed region."""
+    from paper_2305_05920_amd.kvm import KVManager
+    from paper_2305_05920_amd.sched import Scheduler
+    if cfg.dtype == "f32":
+        return None
+    H, D, B = cfg.num_heads, cfg.head_dim, cfg.block_size
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
+    lens = wl.job_lens(cfg, wl.seed_for(cfg.index, 0)).astype(np.int64)
+    J = cfg.num_jobs
+    W = int(max((lens.max() + B - 1) // B, (waiting_tokens + B - 1) // B)) + 1
+    nb_run = int(((lens + B - 1) // B).sum())
+    nb_wait = waiting_jobs * ((waiting_tokens + B - 1) // B)
+    nblocks, nslots = nb_run + nb_wait + 64, nb_wait + 64
+    # the cache contents do not matter for time, but they must be finite numbers: zeros
+    mem = torch.zeros((nblocks, 2 * H * B * D), dtype=tdt, device="cuda")
+    pool = fs.Pool(cfg.dtype, H, D, nblocks, num_host_blocks=nslots, device_mem=mem)
+    sched = Scheduler(6, 1.0, 1, 1e9, J)
+    kvm = KVManager([pool], sched, nblocks, nslots, W, max_batch=J)
+    running = list(range(J))
+    for j in running:
+        assert kvm.admit(j, int(lens[j]))
+        sched.add_job(j, 0.5, 0.5)
+        kvm.advance(j, int(lens[j]) - 1)                  # the step appends the last token
+    rng = np.random.default_rng(11)
+    for w in range(waiting_jobs):                         # waiting jobs spread over the lower queues
+        jid = J + w
+        assert kvm.admit(jid, waiting_tokens)
+        sched.add_job(jid, float(rng.choice([1.5, 3.0, 6.0, 12.0])), 1.0)
+        kvm.advance(jid, waiting_tokens)
+    block_bytes = pool.block_bytes
+    table = torch.from_numpy(kvm.table_rows(running)).cuda()
+    d_before = torch.from_numpy((lens - 1).astype(np.int32)).cuda()
+    d_lens = torch.from_numpy(lens.astype(np.int32)).cuda()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    q, k_new, v_new = (torch.randn((J, H, D), generator=g, device="cuda").to(tdt) for _ in range(3))
+    out = torch.empty((J, H, D), dtype=torch.float32, device="cuda")
+    lens_max = int(lens.max())
 
-    def run(n, first):
-        for i in range(n):
-            pool = reps.pools[(first + i) % reps.R]
-            fs.fs_pool_offload(pool, ids, slots, stream=side)
-            fs.fs_pool_upload(pool, slots, ids, stream=side)
-            reps.run_step(first + i)
-    run(warmup, 0)
+    def step():
+        fs.fs_kv_append(pool, table, d_before, k_new, v_new)
+        fs.fs_decode_attention(q, pool, table, d_lens, out, max_len_hint=lens_max)
+
+    def timed(rate):
+        bo0, bi0, _ = kvm.stats()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        pool.profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            marks[i].record()
+            if rate:
+                kvm.retire()
+                if i % 2 == 0:
+                    kvm.start_swaps(running, want_free=kvm.free_blocks + rate)
+                else:
+                    kvm.start_swaps(running, want_free=0)
+            step()
+        marks[steps].record()
+        torch.cuda.current_stream().synchronize()
+        wall = time.perf_counter() - t0
+        kvm.retire(wait=True)
+        t_all = time.perf_counter() - t0
+        prof = pool.profile_collect()
+        pool.profile_enable(False)
+        per = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+        bo, bi, _ = kvm.stats()
+        return {"blocks_asked_per_swap_step": rate, "ms_per_step_median": float(np.median(per)),
+                "ms_per_step_mean_wall": wall * 1e3 / steps,
+                "attention_kernel_ms": prof["attention"]["ms"] / max(prof["attention"]["launches"], 1),
+                "gb_per_s_to_host": (bo - bo0) * block_bytes / t_all / 1e9,
+                "gb_per_s_from_host": (bi - bi0) * block_bytes / t_all / 1e9,
+                "blocks_out": bo - bo0, "blocks_in": bi - bi0, "seconds_until_copies_done": t_all}
+
+    for _ in range(warmup):
+        step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(steps, warmup)
-    torch.cuda.current_stream().synchronize()
-    t_compute = time.perf_counter() - t0
-    side.synchronize()
-    t_all = time.perf_counter() - t0
-    return {"blocks_each_way_per_step": int(len(ids)), "block_bytes": int(block_bytes),
-            "ms_per_step_compute_stream": t_compute * 1e3 / steps, "ms_per_step_until_copies_done": t_all * 1e3 / steps,
-            "host_link_gbps": 2 * len(ids) * block_bytes * steps / t_all / 1e9}
+    rows = [timed(0)]
+    base = rows[0]["ms_per_step_median"]
+    # rates from a trickle to more than the link carries in one step
+    est_step_s = base * 1e-3
+    for gbps in (5, 10, 20, 40, 80):
+        rate = max(1, int(gbps * 1e9 * 2 * est_step_s / block_bytes))
+        rows.append(timed(rate))
+    for r in rows:
+        r["step_time_vs_no_swaps"] = r["ms_per_step_median"] / base
+    pool.check()
+    kvm.close()
+    sched.close()
+    pool.close()
+    res = {"workload": f"{cfg.name} batch decoding while {waiting_jobs} waiting jobs of {waiting_tokens} tokens are swapped "
+                       f"by the cache manager in ENST order", "block_bytes": block_bytes, "rates": rows}
+    log(json.dumps(res))
+    return res
+
+
+MIN_TIMED_STEPS = 50
 
 
 def time_steps(torch, reps, steps, warmup):
+    """`warmup` untimed steps, then max(steps, 50) timed ones between two synchronisations.  Every
+    step is bracketed by events on the stream the kernels run on; returns the median step time,
+    the wall-clock mean over the same steps, the minimum and the number of steps timed."""
+    n = max(int(steps), MIN_TIMED_STEPS)
     for i in range(warmup):
         reps.run_step(i)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
+    for i in range(n):
+        marks[i].record()
         reps.run_step(warmup + i)
+    marks[n].record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / steps
-
-
-def time_step_chunks(torch, reps, chunks=20, per_chunk=20):
-    """Median and minimum of the step time over chunks of consecutive steps (each chunk timed like
-    the headline: wall clock between two synchronisations)."""
-    vals = []
-    for c in range(chunks):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(per_chunk):
-            reps.run_step(c * per_chunk + i)
-        torch.cuda.synchronize()
-        vals.append((time.perf_counter() - t0) * 1e3 / per_chunk)
-    return {"median_ms": float(np.median(vals)), "min_ms": float(np.min(vals)), "chunks": chunks,
-            "steps_per_chunk": per_chunk}
+    wall_ms = (time.perf_counter() - t0) * 1e3 / n
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n)])
+    return {"median_ms": float(np.median(per_step)), "mean_wall_ms": wall_ms, "min_ms": float(per_step.min()),
+            "timed_steps": n}
 
 
 def read_ceiling(fs, torch, nbytes=4 << 30, reps=5):
@@ -350,7 +411,7 @@ def cpu_baseline(reps, budget_s=12.0):
         return lc
 
     times, out, spent = [], None, 0.0
-    while spent < budget_s and len(times) < 200:
+    while (spent < budget_s and len(times) < 200) or not times:
         lc = fresh()
         t0 = time.perf_counter()
         out = lc.decode_step(k_new, v_new, step.q)
@@ -464,7 +525,8 @@ def prefill_phase(fs, torch, wl, cfg, reps, log, with_cpu=True):
 
 
 def load_traffic(cfg_name):
-    """HBM bytes per attention launch measured with rocprofv3 --pmc (committed summary)."""
+    """HBM bytes per attention launch measured with rocprofv3 --pmc on this preset (the committed
+    summary of that run: profiles/attn_partition_<preset>_traffic.txt), or None."""
     path = os.path.join(ROOT, "profiles", f"attn_partition_{cfg_name}_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -477,6 +539,13 @@ def load_traffic(cfg_name):
         return float(vals["hbm_bytes_per_launch"])
     except (KeyError, ValueError):
         return None
+
+
+def roofline_of(cfg, alg_bytes, attn_ms):
+    achieved = alg_bytes / (attn_ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": load_traffic(cfg.name),
+            "kernel": "fs_attn_partition_kernel", "kernel_ms": attn_ms, "alg_bytes_per_launch": alg_bytes}
 
 
 def main():
@@ -500,6 +569,7 @@ def main():
     ap.add_argument("--only-prefill", action="store_true", help="measure the initialization phase alone")
     ap.add_argument("--no-serving-run", action="store_true", help="skip the multi-iteration scheduler-driven run")
     ap.add_argument("--only-serving-run", action="store_true", help="run the scheduler-driven loop alone")
+    ap.add_argument("--only-swap-overlap", action="store_true", help="time the steps beside the cache manager's swaps alone")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the plain stream read/copy kernels over 1 GiB (scale of hardware byte counters)")
     args = ap.parse_args()
@@ -532,25 +602,33 @@ def main():
         log("calibration: 3x fs_stream_read_kernel and 3x fs_stream_copy_kernel over 1 GiB")
         del src, dst
 
-    def measure(idx, steps, warmup, with_cpu):
-        cfg = wl.CONFIGS[idx] if not args.dtype else wl.CONFIGS[idx].scaled(dtype=args.dtype)
+    def config_of(idx):
+        return wl.CONFIGS[idx] if not args.dtype else wl.CONFIGS[idx].scaled(dtype=args.dtype)
+
+    def measure(idx, steps, warmup, cpu_budget_s, extras):
+        """One preset: the two-call step (the headline form) and the fused step, each timed over at
+        least 50 steps; kernel durations from launch-attached events; its own roofline object and
+        its own CPU baseline (the oracle's whole step on the same inputs, one thread)."""
+        cfg = config_of(idx)
         reps = Replicas(fs, torch, wl, cfg, 0, args.footprint_gb * 1e9, pool_kw, log)
         try:
             if args.wgs_per_cu:
                 for p in reps.pools:
                     p.set_param("wgs_per_cu", args.wgs_per_cu)
+            nk = max(reps.R * 4, min(max(steps, MIN_TIMED_STEPS), 200))
             reps.fused = True
-            ms_f = time_steps(torch, reps, steps, warmup)
-            kt_f = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
+            t_f = time_steps(torch, reps, steps, warmup)
+            kt_f = kernel_times(torch, reps, nk)
             reps.fused = False
-            ms = time_steps(torch, reps, steps, warmup)
-            kt = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
-            res = {"workload": cfg.name, "ms_per_step": ms, "job_tokens_per_s": cfg.num_jobs / (ms / 1e3),
-                   "kernel_ms": kt, "alg_bytes": reps.alg_bytes, "sum_len": int(reps.step.total_tokens),
-                   "replicas": reps.R,
-                   "attention_gbps": reps.alg_bytes / (kt["attention"] * 1e-3) / 1e9,
-                   "fused_step": {"ms_per_step": ms_f, "job_tokens_per_s": cfg.num_jobs / (ms_f / 1e3),
-                                  "kernel_ms": kt_f,
+            t = time_steps(torch, reps, steps, warmup)
+            kt = kernel_times(torch, reps, nk)
+            ms = t["median_ms"]
+            res = {"workload": f"configs[{cfg.index}] {cfg.name}", "ms_per_step": ms, "step_timing": t,
+                   "job_tokens_per_s": cfg.num_jobs / (ms / 1e3),
+                   "kernel_ms": kt, "sum_len": int(reps.step.total_tokens), "replicas": reps.R,
+                   "roofline": roofline_of(cfg, reps.alg_bytes, kt["attention"]),
+                   "fused_step": {"ms_per_step": t_f["median_ms"], "step_timing": t_f,
+                                  "job_tokens_per_s": cfg.num_jobs / (t_f["median_ms"] / 1e3), "kernel_ms": kt_f,
                                   "attention_gbps": reps.alg_bytes / (kt_f["attention"] * 1e-3) / 1e9}}
             if not args.no_merge_in_kernel:
                 # the same two step forms with the cut pairs merged by the attention kernel
@@ -558,60 +636,61 @@ def main():
                 for p in reps.pools:
                     p.set_param("merge_in_kernel", 1)
                 reps.fused = True
-                ms_mf = time_steps(torch, reps, steps, warmup)
+                t_mf = time_steps(torch, reps, steps, warmup)
                 reps.fused = False
-                ms_m = time_steps(torch, reps, steps, warmup)
-                kt_m = kernel_times(torch, reps, max(reps.R * 4, min(steps, 200)))
+                t_m = time_steps(torch, reps, steps, warmup)
+                kt_m = kernel_times(torch, reps, nk)
                 for p in reps.pools:
                     p.set_param("merge_in_kernel", 0)
-                res["merge_in_kernel"] = {"ms_per_step": ms_m, "fused_ms_per_step": ms_mf, "kernel_ms": kt_m}
-            if idx == args.config and not args.no_warm_cache:
-                res["ms_per_step_chunks"] = time_step_chunks(torch, reps)
+                res["merge_in_kernel"] = {"ms_per_step": t_m["median_ms"], "fused_ms_per_step": t_mf["median_ms"],
+                                          "kernel_ms": kt_m}
+            if extras and not args.no_warm_cache:
                 res["ms_per_step_warm_cache"] = time_steps_warm(torch, reps, steps, warmup)
-            if not args.no_swap_overlap:
-                res["swap_overlap"] = swap_overlap(torch, reps, max(50, steps // 2), max(5, warmup // 2))
             if not args.no_graph:
                 try:
-                    res["ms_per_step_graph"] = graph_ms(torch, reps, steps)
+                    res["ms_per_step_graph"] = graph_ms(torch, reps, max(steps, MIN_TIMED_STEPS))
                 except Exception as e:  # graph capture is an extra, never the headline
                     log(f"graph replay skipped: {e}")
-            # check the result of the last step against the oracle on the way
+            # the result of the last step against the oracle, and the oracle's own speed
             got = reps.out.cpu().numpy()
-            base = None
-            if with_cpu:
-                base, ref = cpu_baseline(reps)
+            if cpu_budget_s > 0:
+                base, ref = cpu_baseline(reps, cpu_budget_s)
+                res["cpu_baseline"] = base
                 diff = got.astype(np.float64) - ref
                 res["max_abs_err"] = float(np.abs(diff).max())
                 res["rel_l2_err"] = float(np.linalg.norm(diff) / np.linalg.norm(ref))
                 rows = np.linalg.norm(diff, axis=-1) / np.maximum(np.linalg.norm(ref, axis=-1), 1e-300)
                 res["worst_row_rel_l2_err"] = float(rows.max())      # worst single (job, head) row
+            else:
+                res["cpu_baseline"] = None
             for p in reps.pools:
                 p.check()
             log(json.dumps(res))
-            return res, base
+            return res
         finally:
             reps.close()
 
+    cfg = config_of(args.config)
     if args.only_serving_run:
-        cfg = wl.CONFIGS[args.config] if not args.dtype else wl.CONFIGS[args.config].scaled(dtype=args.dtype)
         print(json.dumps(serving_run(fs, torch, wl, cfg, log)), flush=True)
         return
     if args.only_prefill:
-        cfg = wl.CONFIGS[args.config] if not args.dtype else wl.CONFIGS[args.config].scaled(dtype=args.dtype)
         print(json.dumps(prefill_phase(fs, torch, wl, cfg, 20, log, not args.no_cpu_baseline)), flush=True)
         return
-    main_res, base = measure(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
+    if args.only_swap_overlap:
+        print(json.dumps(swap_overlap(fs, torch, wl, cfg, log)), flush=True)
+        return
+    with_cpu = not args.no_cpu_baseline
+    main_res = measure(args.config, args.steps, args.warmup, 12.0 if with_cpu else 0.0, True)
     others = []
     for tok in [t for t in args.also.split(",") if t.strip()]:
         idx = int(tok)
         if idx == args.config:
             continue
-        r, _ = measure(idx, max(50, args.steps // 4), max(10, args.warmup // 4), False)
-        others.append(r)
+        others.append(measure(idx, max(MIN_TIMED_STEPS, args.steps // 4), max(10, args.warmup // 4),
+                              3.0 if with_cpu else 0.0, False))
 
-    cfg = wl.CONFIGS[args.config] if not args.dtype else wl.CONFIGS[args.config].scaled(dtype=args.dtype)
-    attn_ms = main_res["kernel_ms"]["attention"]
-    achieved = main_res["alg_bytes"] / (attn_ms * 1e-3) / 1e9
+    worst = min([main_res] + others, key=lambda r: r["roofline"]["frac"])
     line = {
         "metric": METRIC,
         "value": main_res["job_tokens_per_s"],
@@ -620,6 +699,10 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"],
+        "ms_per_step_is": f"median over {main_res['step_timing']['timed_steps']} steps, each bracketed by events on the "
+                          "kernels' stream (at least 50 whatever --steps says); step_timing.mean_wall_ms is the wall "
+                          "clock over the same steps",
+        "step_timing": main_res["step_timing"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -629,18 +712,16 @@ def main():
                                f"{cfg.head_dim}, {cfg.dtype}, block 16, sum(L)={main_res['sum_len']}",
                    "step": "fs_kv_append + fs_decode_attention (partition pass + combine)",
                    "pool_replicas": main_res["replicas"]},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": load_traffic(cfg.name),
-                     "kernel": "fs_attn_partition_kernel", "kernel_ms": attn_ms,
-                     "alg_bytes_per_launch": main_res["alg_bytes"]},
-        "cpu_baseline": base,
+        "roofline": main_res["roofline"],
+        # the lowest fraction of the HBM peak among the presets of this line, and whose it is
+        "worst_roofline": {"workload": worst["workload"], "frac": worst["roofline"]["frac"],
+                           "achieved": worst["roofline"]["achieved"], "kernel_ms": worst["roofline"]["kernel_ms"]},
+        "cpu_baseline": main_res["cpu_baseline"],
         "kernel_ms": main_res["kernel_ms"],
         "fused_step": main_res["fused_step"],
         "merge_in_kernel": main_res.get("merge_in_kernel"),
-        "swap_overlap": main_res.get("swap_overlap"),
         "ms_per_step_graph": main_res.get("ms_per_step_graph"),
         "ms_per_step_warm_cache": main_res.get("ms_per_step_warm_cache"),
-        "ms_per_step_chunks": main_res.get("ms_per_step_chunks"),
         "max_abs_err": main_res.get("max_abs_err"),
         "rel_l2_err": main_res.get("rel_l2_err"),
         "worst_row_rel_l2_err": main_res.get("worst_row_rel_l2_err"),
@@ -648,12 +729,16 @@ def main():
     }
     if not args.no_warm_cache:
         ceil = read_ceiling(fs, torch)
-        line["roofline"]["practical_read_ceiling_gbps"] = ceil
-        line["roofline"]["frac_of_practical_ceiling"] = achieved / ceil
+        for r in [line] + others:
+            r["roofline"]["practical_read_ceiling_gbps"] = ceil
+            r["roofline"]["frac_of_practical_ceiling"] = r["roofline"]["achieved"] / ceil
+    if not args.no_swap_overlap:
+        line["swap_overlap"] = [swap_overlap(fs, torch, wl, config_of(i), log) for i in (1, 3)
+                                if config_of(i).dtype != "f32"]
     if not args.no_serving_run:
         line["serving_run"] = serving_run(fs, torch, wl, cfg, log)
     if not args.no_prefill:
-        line["prefill_phase"] = prefill_phase(fs, torch, wl, cfg, 20, log, not args.no_cpu_baseline)
+        line["prefill_phase"] = prefill_phase(fs, torch, wl, cfg, 20, log, with_cpu)
     print(json.dumps(line), flush=True)
 
 

@@ -66,6 +66,10 @@ constexpr int kJobsPerThread = 4;
 constexpr int kMaxJobsPerLaunch = kThreads * kJobsPerThread;  // 1024
 constexpr int kWindowBlocks = 128;                            // table entries a wave keeps in LDS
 constexpr int kWindowSteps = kWindowBlocks / kStepBlocks;
+#ifndef FS_KEY_WRITE_BYTES
+#define FS_KEY_WRITE_BYTES 64
+#endif
+constexpr int kKeyWriteBytes = FS_KEY_WRITE_BYTES;  // bytes an appended key piece is written as (its aligned neighbourhood)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -892,7 +896,23 @@ __device__ __forceinline__ void append_block(
     const int slot = pos % kBlockTokens;
     const size_t chunk = (size_t)kBlockTokens * D * EB;
     char *blk = pool + (size_t)bid * (2 * (size_t)H * chunk);
-    *(u32x4 *)(blk + (size_t)h * chunk + ((size_t)vec * kBlockTokens + slot) * 16) = kv;
+    // The key order puts a token's sixteen 16-byte pieces into sixteen different cache lines.
+    // Written as they are, they reach memory as partial writes, which the memory side turns
+    // into read-modify-write cycles that the kernel after this one ends up waiting for
+    // (measured: up to 14 us of a 280 us attention kernel for 82 k pieces).  So each piece
+    // goes out as the whole aligned kWriteBytes group of neighbouring slots it lies in, read
+    // first: the line is written in full.  The neighbours are this job's own earlier tokens
+    // (or not yet written), and no other thread writes this group in this launch.
+    constexpr int kGroupSlots = kKeyWriteBytes / 16;
+    u32x4 *grp = (u32x4 *)(blk + (size_t)h * chunk + ((size_t)vec * kBlockTokens + (slot & ~(kGroupSlots - 1))) * 16);
+    u32x4 g[kGroupSlots];
+#pragma unroll
+    for (int i = 0; i < kGroupSlots; ++i) g[i] = grp[i];
+#pragma unroll
+    for (int i = 0; i < kGroupSlots; ++i)
+        if (i == (slot & (kGroupSlots - 1))) g[i] = kv;
+#pragma unroll
+    for (int i = 0; i < kGroupSlots; ++i) grp[i] = g[i];
     *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
 }
 
