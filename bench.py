@@ -169,30 +169,40 @@ def swap_overlap(fs, torch, wl, cfg, log, steps=150, warmup=20, waiting_jobs=48,
         fs.fs_kv_append(pool, table, d_before, k_new, v_new)
         fs.fs_decode_attention(q, pool, table, d_lens, out, max_len_hint=lens_max)
 
+    def drive(rate, n):
+        for i in range(n):
+            if rate:
+                kvm.retire()
+                # even steps ask for `rate` blocks more than are free or on their way out: waiting
+                # jobs leave, latest next scheduled time first; odd steps ask for nothing: those
+                # whose blocks have arrived in host memory come back, earliest first
+                kvm.start_swaps(running, want_free=(kvm.free_blocks + rate) if i % 2 == 0 else 0)
+            yield i
+            step()
+
     def timed(rate):
         bo0, bi0, _ = kvm.stats()
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-        pool.profile_enable(True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(steps):
+        for i in drive(rate, steps):
             marks[i].record()
-            if rate:
-                kvm.retire()
-                if i % 2 == 0:
-                    kvm.start_swaps(running, want_free=kvm.free_blocks + rate)
-                else:
-                    kvm.start_swaps(running, want_free=0)
-            step()
         marks[steps].record()
         torch.cuda.current_stream().synchronize()
         wall = time.perf_counter() - t0
         kvm.retire(wait=True)
         t_all = time.perf_counter() - t0
-        prof = pool.profile_collect()
-        pool.profile_enable(False)
         per = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
         bo, bi, _ = kvm.stats()
+        # the kernels' own durations from a second, shorter pass with launch-attached events
+        # (recording them costs host time, so the step time above is taken without)
+        pool.profile_enable(True)
+        for _ in drive(rate, steps // 3):
+            pass
+        torch.cuda.synchronize()
+        kvm.retire(wait=True)
+        prof = pool.profile_collect()
+        pool.profile_enable(False)
         return {"blocks_asked_per_swap_step": rate, "ms_per_step_median": float(np.median(per)),
                 "ms_per_step_mean_wall": wall * 1e3 / steps,
                 "attention_kernel_ms": prof["attention"]["ms"] / max(prof["attention"]["launches"], 1),
@@ -205,11 +215,9 @@ def swap_overlap(fs, torch, wl, cfg, log, steps=150, warmup=20, waiting_jobs=48,
     torch.cuda.synchronize()
     rows = [timed(0)]
     base = rows[0]["ms_per_step_median"]
-    # rates from a trickle to more than the link carries in one step
-    est_step_s = base * 1e-3
-    for gbps in (5, 10, 20, 40, 80):
-        rate = max(1, int(gbps * 1e9 * 2 * est_step_s / block_bytes))
-        rows.append(timed(rate))
+    per_job = (waiting_tokens + B - 1) // B
+    for jobs_at_once in (1, 2, 4, 8, 16, 32):           # from a trickle to more than the link carries
+        rows.append(timed(per_job * jobs_at_once))
     for r in rows:
         r["step_time_vs_no_swaps"] = r["ms_per_step_median"] / base
     pool.check()

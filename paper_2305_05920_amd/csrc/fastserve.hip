@@ -37,23 +37,6 @@
 
 #include "fastserve.h"
 
-// Experiments may pin the attention kernel's register budget: -DFS_ATTN_WAVES_PER_EU=n
-#ifdef FS_ATTN_WAVES_PER_EU
-#define FS_ATTN_OCCUPANCY_ATTR __attribute__((amdgpu_waves_per_eu(FS_ATTN_WAVES_PER_EU, FS_ATTN_WAVES_PER_EU)))
-#else
-#define FS_ATTN_OCCUPANCY_ATTR
-#endif
-
-// Experiments may record per-wave timestamps of the attention kernel: -DFS_TRACE
-#ifdef FS_TRACE
-#define FS_TRACE_STAMP(slot)                                                              \
-    do {                                                                                   \
-        if (lane == 0) trace_buf[((size_t)blockIdx.x * kWavesPerWg + wave) * 8 + (slot)] = wall_clock64(); \
-    } while (0)
-#else
-#define FS_TRACE_STAMP(slot) do { } while (0)
-#endif
-
 namespace {
 
 constexpr int kBlockTokens = 16;       // tokens per pool block
@@ -66,10 +49,7 @@ constexpr int kJobsPerThread = 4;
 constexpr int kMaxJobsPerLaunch = kThreads * kJobsPerThread;  // 1024
 constexpr int kWindowBlocks = 128;                            // table entries a wave keeps in LDS
 constexpr int kWindowSteps = kWindowBlocks / kStepBlocks;
-#ifndef FS_KEY_WRITE_BYTES
-#define FS_KEY_WRITE_BYTES 64
-#endif
-constexpr int kKeyWriteBytes = FS_KEY_WRITE_BYTES;  // bytes an appended key piece is written as (its aligned neighbourhood)
+constexpr int kKeyWriteBytes = 64;  // bytes an appended key piece is written as (its aligned neighbourhood)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -281,14 +261,11 @@ __device__ __forceinline__ void merge_pair(const float *part_acc, const float *p
 // sixteen 16-byte pieces per key row, mixed into the read stream here, cost more than
 // the same writes after it.
 template <typename E, int D, bool kFused>
-__global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_partition_kernel(
+__global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
     const uint32_t *__restrict__ q, const char *pool, char *pool_w, const char *__restrict__ k_new,
     const char *__restrict__ v_new, const int32_t *__restrict__ table, const int32_t *__restrict__ lens,
     float *__restrict__ out, float *part_acc, float *part_ml,
     int32_t *__restrict__ plan, int32_t *__restrict__ err, int32_t *pair_cnt, AttnShape sh
-#ifdef FS_TRACE
-    , unsigned long long *__restrict__ trace_buf
-#endif
     )
 {
     constexpr int X = 16 / E::kBytes;        // elements per 16-byte vector
@@ -313,7 +290,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     const int J = sh.num_jobs, H = sh.num_heads;
     const int max_len = sh.table_stride * kBlockTokens;
     const size_t block_bytes = (size_t)2 * H * kChunkBytes;
-    FS_TRACE_STAMP(0);
 
     // ---- prefix sum of steps per job, in LDS ----
     int st[kJobsPerThread];
@@ -392,7 +368,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     const long long lo = range_lo(gw, S, nw);
     const long long hi = range_lo(gw + 1, S, nw);
     if (lo >= hi) return;
-    FS_TRACE_STAMP(1);
 
     const int r = lane >> 4;   // scoring: which of the step's 4 blocks
     const int s = lane & 15;   //          which slot of that block
@@ -457,7 +432,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         fetch_window(trow, kt, w0, w1);
         store_window(w0, w1);
     }
-    FS_TRACE_STAMP(6);
     // the job after this one: its length and first table window are asked for long
     // before the walk reaches it (registers that only the job change below touches)
     int nj = next_job(j);
@@ -547,16 +521,11 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
     }
     // (keys first, then values, here as in the loop: the waits count loads in issue order)
     __builtin_amdgcn_sched_barrier(0);
-    FS_TRACE_STAMP(7);
     issue_values(bid, j, h, k, L, NB, false);
     // fused append: q, key and value vectors of the new token of the pair being finished
     u32x4 xq = u32x4{0u, 0u, 0u, 0u}, xk = xq, xv = xq;
     int xbid = 0;
     int k_begin = k;  // first step of the current (job, head) that this wave handles
-    FS_TRACE_STAMP(2);
-#ifdef FS_TRACE
-    bool first_unit = true;
-#endif
 
     for (long long u = lo; u < hi; ++u) {
         const bool last_of_pair = (k == steps - 1);
@@ -581,14 +550,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
             // and then waits for every load in flight, the next values included.
             asm volatile("" : "+v"(sc));
         }
-#ifdef FS_TRACE
-        if (first_unit) {
-            if (sc == 12345.678f) trace_buf[0] = 0;  // keeps the stamp behind the scores
-            FS_TRACE_STAMP(3);
-            first_unit = false;
-        }
-        if (last_of_range) FS_TRACE_STAMP(4);
-#endif
 
         // ---- which unit comes next.  Done here, with nothing of this unit in flight yet:
         // the rare table reloads below wait for their own data only ----
@@ -694,12 +655,6 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
                 const float p_new = __builtin_amdgcn_exp2f(s_new - m_ref);
-#ifdef FS_DEBUG_EXTRA
-                if (lane == 0) {
-                    float *dbg = part_acc + (size_t)(j_cur * H + h_cur) * 8;
-                    dbg[0] = m_run; dbg[1] = s_new; dbg[2] = p_new; dbg[3] = alpha; dbg[4] = l_lane; dbg[5] = acc[0];
-                }
-#endif
                 l_lane = l_lane * alpha + (lane == 0 ? p_new : 0.f);
 #pragma unroll
                 for (int i = 0; i < X; ++i) acc[i] *= alpha;
@@ -736,17 +691,7 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 } else {
                     const size_t slot = (size_t)gw * 2 + (k_begin > 0 ? 0 : 1);
                     float *o = part_acc + slot * D + (size_t)vc * X;
-                    if (sh.merge) {
-                        // read by another wave of this launch, possibly on another compute die:
-                        // agent-scope stores go through to memory instead of resting in this die's L2
-#pragma unroll
-                        for (int i = 0; i < X; ++i)
-                            __hip_atomic_store(o + i, acc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (lane == 0) {
-                            __hip_atomic_store(part_ml + slot * 2, m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            __hip_atomic_store(part_ml + slot * 2 + 1, l_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        }
-                    } else {
+                    {
 #pragma unroll
                         for (int i = 0; i < X; ++i) o[i] = acc[i];
                         if (lane == 0) {
@@ -764,12 +709,14 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
         }
     }
     // ---- merge mode: the last wave to finish its share of a cut pair merges the pair ----
-    // Every wave that holds a share publishes it: its partial went out with agent-scope
-    // stores; once they have completed it adds its unit count (agent-scope atomic) to the
-    // pair's counter, which lives at the index of the pair's first wave (a wave is the first
-    // wave of one cut pair at most).  The wave whose add completes the pair's step count is
-    // the last: it reads the partials (agent-scope loads), merges, and sets the counter back
-    // to zero for the next launch.  No wave ever waits for another.
+    // Every wave that holds a share of a pair cut across waves has left a partial.  It then adds
+    // its number of units to the pair's counter, which lives at the index of the pair's first
+    // wave (a wave is the first wave of one cut pair at most), with release order at device
+    // scope: whoever sees the sum sees the partial.  The wave whose add completes the pair's
+    // step count is the last: it acquires at device scope, reads the partials, merges, and sets
+    // the counter back to zero for the next launch.  No wave ever waits for another.  The release
+    // writes this compute die's modified cache lines back, which costs time (tens of
+    // microseconds on the presets); the knob is off by default.
     // Which pairs those are follows from the range alone: the pair unit lo lies in, if lo is
     // not its first unit (this wave's slot 0), and the pair unit hi-1 lies in, if it began
     // inside the range and goes on past it (slot 1).
@@ -796,29 +743,23 @@ __global__ __launch_bounds__(kThreads) FS_ATTN_OCCUPANCY_ATTR void fs_attn_parti
                 cut_mine[1] = kk + 1;
             }
         }
-        // the partial stores above were agent-scope (written through); all that is left to do
-        // before the counter add is to wait until they have completed
-        if (cut_have[0] || cut_have[1]) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // for the compiler: stores stay above
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // for the machine: stores have completed
-        }
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             if (!cut_have[c]) continue;
             const long long wa = c ? gw : wave_of_unit(cut_u0[c], S, nw);
             int old = 0;
+            wave_lds_sync();  // every lane's stores of the partial come before lane 0's release
             if (lane == 0)
-                old = __hip_atomic_fetch_add(pair_cnt + wa, cut_mine[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                old = __hip_atomic_fetch_add(pair_cnt + wa, cut_mine[c], __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
             old = __builtin_amdgcn_readfirstlane(old);
             if (old + cut_mine[c] == cut_steps[c]) {
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // keeps the loads below behind the add
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // every lane's loads below come after the add
                 merge_pair<D, true>(part_acc, part_ml, cut_u0[c], cut_steps[c], S, nw,
                                     out + (size_t)cut_jh[c] * D, lane);
                 if (lane == 0) __hip_atomic_store(pair_cnt + wa, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
-    FS_TRACE_STAMP(5);
 }
 
 // ------------------------------------------------------------------------------------
@@ -911,9 +852,10 @@ __device__ __forceinline__ void append_block(
 #pragma unroll
     for (int i = 0; i < kGroupSlots; ++i)
         if (i == (slot & (kGroupSlots - 1))) g[i] = kv;
+    // (non-temporal stores: the rows are next read by another kernel, from memory)
 #pragma unroll
-    for (int i = 0; i < kGroupSlots; ++i) grp[i] = g[i];
-    *(u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16) = vv;
+    for (int i = 0; i < kGroupSlots; ++i) __builtin_nontemporal_store(g[i], grp + i);
+    __builtin_nontemporal_store(vv, (u32x4 *)(blk + (size_t)H * chunk + (size_t)h * chunk + (size_t)slot * D * EB + (size_t)vec * 16));
 }
 
 // ------------------------------------------------------------------------------------
@@ -1160,9 +1102,6 @@ struct fs_pool {
     PfItem *pf_items = nullptr;  // work list of the prompt-attention launches: count, then entries
     int32_t *err = nullptr;
     char *static_scratch = nullptr;  // this device's copy of fs_static_scratch (device address)
-#ifdef FS_TRACE
-    unsigned long long *trace = nullptr;
-#endif
     bool profiling = false;
     std::vector<ProfileRecord> records;
     std::vector<ProfileRecord> spare;
@@ -1210,10 +1149,6 @@ int alloc_scratch(fs_pool *p) {
     if (hipMalloc((void **)&p->pair_cnt, (size_t)waves * sizeof(int32_t)) != hipSuccess) return FS_ERR_OOM;
     if (hipMemset(p->pair_cnt, 0, (size_t)waves * sizeof(int32_t)) != hipSuccess) return FS_ERR_HIP;
     p->waves_cap = (int)waves;
-#ifdef FS_TRACE
-    if (hipMalloc((void **)&p->trace, (size_t)waves * 8 * sizeof(unsigned long long)) != hipSuccess) return FS_ERR_OOM;
-    (void)hipMemset(p->trace, 0, (size_t)waves * 8 * sizeof(unsigned long long));
-#endif
     return FS_OK;
 }
 
@@ -1291,9 +1226,6 @@ int launch_attention(fs_pool *p, const AttnScratch &sc, const void *q, const voi
                   (const uint32_t *)q, (const char *)p->mem, write_in_kernel ? p->mem : (char *)nullptr,
                   (const char *)k_new, (const char *)v_new, table, lens, out, sc.part_acc, sc.part_ml, sc.plan,
                   p->err, p->pair_cnt, sh
-#ifdef FS_TRACE
-                  , p->trace
-#endif
     );
     if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
     if (sh.merge) return FS_OK;
@@ -1781,22 +1713,7 @@ int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups,
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
-#ifdef FS_TRACE
-int fs_debug_trace(fs_pool *p, void *host, size_t bytes)
-{
-    if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
-    size_t cap = (size_t)p->waves_cap * 8 * sizeof(unsigned long long);
-    return hipMemcpy(host, p->trace, bytes < cap ? bytes : cap, hipMemcpyDeviceToHost) == hipSuccess ? FS_OK : FS_ERR_HIP;
-}
-#endif
 
-#ifdef FS_DEBUG_EXTRA
-int fs_debug_partials(fs_pool *p, void *host, size_t bytes)
-{
-    if (hipDeviceSynchronize() != hipSuccess) return FS_ERR_HIP;
-    return hipMemcpy(host, p->part_acc, bytes, hipMemcpyDeviceToHost) == hipSuccess ? FS_OK : FS_ERR_HIP;
-}
-#endif
 
 const char *fs_strerror(int status)
 {
