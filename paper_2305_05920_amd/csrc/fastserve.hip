@@ -483,10 +483,8 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
 
     // Value loads of one unit: its four blocks, four 1 KiB load instructions each.  Rows past
     // the job's last block repeat that block, slots past its last token repeat that token
-    // (weight zero either way).  `dead`: there is no such unit (the range's last unit has no
-    // successor); the loads then read the first 4 KiB of the pool, one hot set of lines for
-    // every wave, instead of sitting behind a branch.
-    auto issue_values = [&](int bidv, int jj, int hh, int kk, int LL, int NBB, bool dead) {
+    // (weight zero either way).
+    auto issue_values = [&](int bidv, int jj, int hh, int kk, int LL, int NBB) {
 #pragma unroll
         for (int b = 0; b < kStepBlocks; ++b) {
             const int bb = __builtin_amdgcn_readlane(bidv, 16 * b);
@@ -498,10 +496,6 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
             // fused, empty cache: nothing of this job is in the pool yet; the loads read the
             // job's own new value row instead (finite data, weight zero), slot 0 below
             if (kFused && LL == 0) vp = v_new + ((size_t)jj * H + hh) * kRowBytes + (size_t)vc * 16;
-            if (dead) {
-                vp = pool + (size_t)vc * 16;
-                left = kBlockTokens;
-            }
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 int slot = i * TPI + vt;
@@ -521,15 +515,18 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
     }
     // (keys first, then values, here as in the loop: the waits count loads in issue order)
     __builtin_amdgcn_sched_barrier(0);
-    issue_values(bid, j, h, k, L, NB, false);
+    issue_values(bid, j, h, k, L, NB);
     // fused append: q, key and value vectors of the new token of the pair being finished
     u32x4 xq = u32x4{0u, 0u, 0u, 0u}, xk = xq, xv = xq;
     int xbid = 0;
     int k_begin = k;  // first step of the current (job, head) that this wave handles
 
-    for (long long u = lo; u < hi; ++u) {
+    // One unit.  The range's last unit (kLast) has no successor: that copy of the body asks for
+    // no further keys, values or q, so the wave leaves as soon as its own data is worked off
+    // (loads to spare would come back behind everything else its compute unit has in flight).
+    auto unit = [&](auto is_last) {
+        constexpr bool last_of_range = decltype(is_last)::value;
         const bool last_of_pair = (k == steps - 1);
-        const bool last_of_range = (u + 1 == hi);
         const int j_cur = j, h_cur = h, L_cur = L;
 
         // ---- scores of this unit's 64 tokens (base 2: scale*log2(e) folded in) ----
@@ -553,7 +550,7 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
 
         // ---- which unit comes next.  Done here, with nothing of this unit in flight yet:
         // the rare table reloads below wait for their own data only ----
-        if (!last_of_range) {
+        if constexpr (!last_of_range) {
             if (!last_of_pair) {
                 ++k;
                 if (k - kt == kWindowSteps) {  // walk on to the next 128 table entries
@@ -586,7 +583,8 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
                 }
             }
         }
-        const int bid_next = row_block(k);
+        int bid_next = 0;
+        if constexpr (!last_of_range) bid_next = row_block(k);
 
         if (kFused && last_of_pair) {
             // the new token's vectors and the block it goes to: asked for now, used at the pair's end
@@ -600,12 +598,9 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
         }
 
         // ---- the next unit's q and keys go in flight ----
-        // (the range's last unit has no successor: its loads are pointed at the first
-        // 4 KiB of the pool, one hot set of lines for every wave, instead of a branch)
-        load_q(j, h);
-        {
+        if constexpr (!last_of_range) {
+            load_q(j, h);
             const char *kp = pool + (size_t)bid_next * block_bytes + (size_t)h * kChunkBytes + (size_t)s * 16;
-            kp = last_of_range ? pool + (size_t)s * 16 : kp;
 #pragma unroll
             for (int i = 0; i < NK; ++i) kr[i] = load_stream(kp + i * (kBlockTokens * 16));
         }
@@ -638,8 +633,7 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
         }
         wave_lds_sync();
         // ---- the next unit's values go in flight (its keys already are) ----
-        issue_values(bid_next, j, h, k, L, NB, last_of_range);
-        bid = bid_next;
+        if constexpr (!last_of_range) issue_values(bid_next, j, h, k, L, NB);
 
         // ---- end of this wave's share of the (job, head) pair ----
         if (last_of_pair || last_of_range) {
@@ -707,7 +701,9 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
             for (int i = 0; i < X; ++i) acc[i] = 0.f;
             k_begin = 0;
         }
-    }
+    };
+    for (long long u = lo; u + 1 < hi; ++u) unit(std::false_type{});
+    unit(std::true_type{});
     // ---- merge mode: the last wave to finish its share of a cut pair merges the pair ----
     // Every wave that holds a share of a pair cut across waves has left a partial.  It then adds
     // its number of units to the pair's counter, which lives at the index of the pair's first
