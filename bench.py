@@ -567,6 +567,8 @@ def main():
     ap.add_argument("--also", type=str, default="2,3,4", help="other presets reported under 'other_workloads'")
     ap.add_argument("--footprint-gb", type=float, default=2.0, help="bytes touched between reuses of a replica")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
+                    help="pool knob for every pool of the run (fs_pool_set_param), e.g. split_unit_cost=4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-swap-overlap", action="store_true", help="skip the steps timed beside block swaps")
@@ -623,6 +625,10 @@ def main():
             if args.wgs_per_cu:
                 for p in reps.pools:
                     p.set_param("wgs_per_cu", args.wgs_per_cu)
+            for kv in args.set:
+                name, val = kv.split("=")
+                for p in reps.pools:
+                    p.set_param(name, int(val))
             nk = max(reps.R * 4, min(max(steps, MIN_TIMED_STEPS), 200))
             reps.fused = True
             t_f = time_steps(torch, reps, steps, warmup)
