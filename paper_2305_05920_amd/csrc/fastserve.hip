@@ -1090,9 +1090,6 @@ struct fs_pool {
     // meets them; 0 (default): the launch that follows it (the combine pass) does, in extra
     // workgroups.  The sixteen 16-byte pieces of a key row cost more inside the read stream.
     int append_in_attention = 0;
-    // prompt attention: 0 = workgroups of 4 waves on 128 query rows; 1 = workgroups of two groups
-    // of 4 waves on 256 query rows that take turns on the matrix cores
-    int prefill_variant = 0;
     int waves_cap = 0;       // waves the partial buffers are sized for
     float *part_acc = nullptr;
     float *part_ml = nullptr;
@@ -1155,8 +1152,7 @@ int alloc_scratch(fs_pool *p) {
 // runtime stamps with the kernel's own start and end (the same span a profiler reports
 // for the dispatch), on the stream the kernel runs on.
 template <typename... Params, typename... Args>
-void launch_kernel_block(fs_pool *p, int kind, void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t s,
-                         Args... args)
+void launch_kernel(fs_pool *p, int kind, void (*kernel)(Params...), dim3 grid, hipStream_t s, Args... args)
 {
     if (p->profiling && kind >= 0) {  // kind < 0: a plain launch, whatever the profiling switch says
         ProfileRecord rec{};
@@ -1171,18 +1167,12 @@ void launch_kernel_block(fs_pool *p, int kind, void (*kernel)(Params...), dim3 g
         }
         if (have) {
             rec.kind = kind;
-            hipExtLaunchKernelGGL(kernel, grid, block, 0, s, rec.start, rec.stop, 0, static_cast<Params>(args)...);
+            hipExtLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, s, rec.start, rec.stop, 0, static_cast<Params>(args)...);
             p->records.push_back(rec);
             return;
         }
     }
-    hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<Params>(args)...);
-}
-
-template <typename... Params, typename... Args>
-void launch_kernel(fs_pool *p, int kind, void (*kernel)(Params...), dim3 grid, hipStream_t s, Args... args)
-{
-    launch_kernel_block(p, kind, kernel, grid, dim3(kThreads), s, args...);
+    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), 0, s, static_cast<Params>(args)...);
 }
 
 // Where one attention call keeps its partial results and its plan: the pool's own buffers, or
@@ -1454,29 +1444,19 @@ static int run_prefill_attention(fs_pool *p, bool write, const int32_t *table, i
     const int G = (H + kXcds - 1) / kXcds;  // head groups: one head per die and group
     hipStream_t s = (hipStream_t)stream;
     const float c = p->scale * 1.4426950408889634f;
-    const bool pp = p->prefill_variant == 1 && D == 128;
-    const int qtile = pp ? kPpQTile : kPfQTile;
     for (int j0 = 0; j0 < J; j0 += kMaxJobsPerLaunch) {
         const int n = (J - j0) < kMaxJobsPerLaunch ? (J - j0) : kMaxJobsPerLaunch;
         launch_kernel(p, FS_KERNEL_PREFILL_PLAN, fs_prefill_plan_kernel, dim3(1), s, offs + j0, n, G,
-                      (long long)total_tokens, qtile, p->pf_items, p->err);
-        // the list cannot be longer than one entry per started query tile of every job and head group
-        long long entries = ((long long)total_tokens / qtile + n) * G;
+                      (long long)total_tokens, p->pf_items, p->err);
+        // the list cannot be longer than one entry per started 128 tokens of every job and head group
+        long long entries = ((long long)total_tokens / kPfQTile + n) * G;
         if (entries > kPfMaxItems) entries = kPfMaxItems;
         const dim3 grid((unsigned)(entries * kXcds));
         const int32_t *ts = write ? table + (size_t)j0 * stride : nullptr;
-#define FS_PF_LAUNCH(E, DD, W)                                                                                    \
-    do {                                                                                                          \
-        if (pp)                                                                                                   \
-            launch_kernel_block(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_pp_kernel<E, W>, grid,            \
-                                dim3(kPpThreads), s, (const char *)q, (const char *)k, (const char *)v,           \
-                                (const PfItem *)p->pf_items, out, H, c, p->mem, ts, stride, p->cfg.num_blocks,    \
-                                p->err);                                                                          \
-        else                                                                                                      \
-            launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD, W>, grid, s,              \
-                          (const char *)q, (const char *)k, (const char *)v, (const PfItem *)p->pf_items, out, H, \
-                          c, p->mem, ts, stride, p->cfg.num_blocks, p->err);                                      \
-    } while (0)
+#define FS_PF_LAUNCH(E, DD, W)                                                                                 \
+    launch_kernel(p, FS_KERNEL_PREFILL_ATTENTION, fs_prefill_attn_kernel<E, DD, W>, grid, s, (const char *)q,   \
+                  (const char *)k, (const char *)v, (const PfItem *)p->pf_items, out, H, c, p->mem, ts, stride, \
+                  p->cfg.num_blocks, p->err)
 #define FS_PF_DISPATCH(W)                                                          \
     do {                                                                           \
         if (p->cfg.dtype == FS_BF16) {                                             \
@@ -1681,11 +1661,6 @@ int fs_pool_set_param(fs_pool *p, const char *name, int32_t value)
         p->merge_in_kernel = value;
         return FS_OK;
     }
-    if (!std::strcmp(name, "prefill_variant")) {
-        if (value < 0 || value > 1) return FS_ERR_INVALID_ARG;
-        p->prefill_variant = value;
-        return FS_OK;
-    }
     return FS_ERR_INVALID_ARG;
 }
 
@@ -1697,7 +1672,6 @@ int fs_pool_get_param(const fs_pool *p, const char *name, int32_t *value)
     else if (!std::strcmp(name, "swap_engine")) *value = p->swap_engine;
     else if (!std::strcmp(name, "merge_in_kernel")) *value = p->merge_in_kernel;
     else if (!std::strcmp(name, "append_in_attention")) *value = p->append_in_attention;
-    else if (!std::strcmp(name, "prefill_variant")) *value = p->prefill_variant;
     else if (!std::strcmp(name, "num_cus")) *value = p->num_cus;
     else if (!std::strcmp(name, "max_jobs_per_launch")) *value = p->max_jobs < kMaxJobsPerLaunch ? p->max_jobs : kMaxJobsPerLaunch;
     else return FS_ERR_INVALID_ARG;

@@ -88,11 +88,11 @@ struct PfItem {
 constexpr int kPfMaxItems = 262144;  // entries the pool's work list holds
 
 // Builds the work list of a launch (one workgroup).  offs[J+1], J <= 1024; G head groups; prompts
-// of at most 65535 query tiles of `qtile` rows (128 or 256, the attention kernel's choice).
+// of at most 65535 query tiles.
 // items[0].t0 receives the entry count, entries follow from items[1].  A job whose offsets
 // decrease or leave [0, total_tokens] raises the flag and gets no entry.
 __global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t *__restrict__ offs, int32_t J,
-                                                                   int32_t G, long long total_tokens, int32_t qtile,
+                                                                   int32_t G, long long total_tokens,
                                                                    PfItem *__restrict__ items,
                                                                    int32_t *__restrict__ err)
 {
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t
         long long acc = 0;
         for (int rk = 0; rk < J; ++rk) {
             s_base[rk] = (int32_t)acc;
-            acc += (long long)((s_len[s_ord[rk]] + qtile - 1) / qtile) * G;
+            acc += (long long)((s_len[s_ord[rk]] + kPfQTile - 1) / kPfQTile) * G;
             if (acc > kPfMaxItems) {  // more work than the list holds: serve what fits, say so
                 atomicOr(err, kErrBadLen);
                 acc = s_base[rk];
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void fs_prefill_plan_kernel(const int32_t
             if (s_base[mid] <= e) lo = mid; else hi = mid;
         }
         const int j = s_ord[lo];
-        const int tiles = (s_len[j] + qtile - 1) / qtile;
+        const int tiles = (s_len[j] + kPfQTile - 1) / kPfQTile;
         const int rem = e - s_base[lo];
         PfItem it;
         it.t0 = s_t0[j];
@@ -224,13 +224,27 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     const int st_row = threadIdx.x / kChunks, st_chunk = threadIdx.x % kChunks;
     u32x4 kr[SP], vr[SP];
 
-    auto load_tile = [&](int kt) {
+    // this thread's byte offset from a tile's first row, per pass (a tile's rows lie
+    // tok_bytes apart; 64 rows of at most 16 MB fit 32 bits)
+    uint32_t st_off[SP];
 #pragma unroll
-        for (int p = 0; p < SP; ++p) {
-            int row = kt * kPfKTile + st_row + p * kRowsPerPass;
-            row = row < s ? row : s - 1;
-            kr[p] = *(const u32x4 *)(kb + (size_t)row * tok_bytes + st_chunk * 16);
-            vr[p] = *(const u32x4 *)(vb + (size_t)row * tok_bytes + st_chunk * 16);
+    for (int p = 0; p < SP; ++p) st_off[p] = (uint32_t)((size_t)(st_row + p * kRowsPerPass) * tok_bytes) + st_chunk * 16;
+    auto load_tile = [&](int kt) {
+        const size_t tile = (size_t)kt * kPfKTile * tok_bytes;  // wave-uniform
+        if (kt * kPfKTile + kPfKTile <= s) {  // the whole tile lies inside the prompt: no address arithmetic per lane
+#pragma unroll
+            for (int p = 0; p < SP; ++p) {
+                kr[p] = *(const u32x4 *)(kb + tile + st_off[p]);
+                vr[p] = *(const u32x4 *)(vb + tile + st_off[p]);
+            }
+        } else {  // the prompt's last tile: rows past its end repeat its last row
+#pragma unroll
+            for (int p = 0; p < SP; ++p) {
+                int row = kt * kPfKTile + st_row + p * kRowsPerPass;
+                row = row < s ? row : s - 1;
+                kr[p] = *(const u32x4 *)(kb + (size_t)row * tok_bytes + st_chunk * 16);
+                vr[p] = *(const u32x4 *)(vb + (size_t)row * tok_bytes + st_chunk * 16);
+            }
         }
     };
     auto store_tile = [&]() {
@@ -344,7 +358,7 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[0][e]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[1][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = fmaxf(mx, pf_other_half(mx));
         const float m_new = fmaxf(m, mx * scale_log2e);  // finite: key 0 is visible to every row
         const float alpha = __builtin_amdgcn_exp2f(m - m_new);
         m = m_new;
@@ -356,8 +370,9 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
             for (int e = 0; e < 16; e += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kh][e], scale_log2e, -m_new));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kh][e + 1], scale_log2e, -m_new));
-                l += p0 + p1;
-                pb[kh * 2 + (e >> 3)][(e & 7) >> 1] = PfMath<E>::pack2(p0, p1);
+                const uint32_t pk = PfMath<E>::pack2(p0, p1);
+                l = PfMath<E>::add_pair(pk, l);  // the denominator sums what the matrix cores will multiply
+                pb[kh * 2 + (e >> 3)][(e & 7) >> 1] = pk;
             }
         if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {  // wave-uniform
 #pragma unroll
@@ -379,7 +394,7 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     }
 
     // the denominators of the two half-waves belong to the same rows
-    l += __shfl_xor(l, 32, 64);
+    l += pf_other_half(l);
     const float inv = 1.f / l;
     // Output: the wave's 32 x D tile goes through LDS in two passes of D/2 columns, so that a
     // row's columns leave in one piece (16 lanes x 16 bytes) instead of 16 bytes per lane.
@@ -387,374 +402,6 @@ __global__ __launch_bounds__(kThreads, 2) void fs_prefill_attn_kernel(
     char *const stage = lds + wave * (32 * kOutStride);
     constexpr int kLanesPerRow = kOutCols / 4;        // lanes that cover a staged row with 16 bytes each
     constexpr int kRowsPerStore = 64 / kLanesPerRow;  // rows one store instruction covers
-    const int out_row = lane / kLanesPerRow, out_col = (lane % kLanesPerRow) * 4;
-    float *const ob = out + ((size_t)t0 + row0) * ((size_t)H * D) + (size_t)h * D;
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-#pragma unroll
-        for (int tt = 0; tt < ND / 2; ++tt) {
-            const int t = pass * (ND / 2) + tt;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                pf_f32x4 w = {o[t][4 * i] * inv, o[t][4 * i + 1] * inv, o[t][4 * i + 2] * inv, o[t][4 * i + 3] * inv};
-                *(pf_f32x4 *)(stage + r * kOutStride + (tt * 32 + 8 * i + 4 * hh) * 4) = w;
-            }
-        }
-        wave_lds_sync();
-#pragma unroll
-        for (int it = 0; it < 32 / kRowsPerStore; ++it) {
-            const int row = it * kRowsPerStore + out_row;
-            const pf_f32x4 w = *(const pf_f32x4 *)(stage + row * kOutStride + out_col * 4);
-            if (row0 + row < s) *(pf_f32x4 *)(ob + (size_t)row * ((size_t)H * D) + pass * kOutCols + out_col) = w;
-        }
-        wave_lds_sync();
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// The same computation with two groups of four waves per workgroup that take turns on the
-// matrix cores (head_dim 128).  A workgroup (512 threads) owns 256 consecutive query rows of
-// one (job, head): group A (waves 0-3) the first 128, group B (waves 4-7) the second 128, a
-// wave 32 rows as above, and both groups walk the same staged key/value tiles.  Time is cut
-// into phases separated by workgroup barriers; in every phase one group does the matrix work
-// of a tile step -- O^T += V^T P^T of the previous tile, then S^T = K Q^T of the current
-// one -- while the other group does its softmax arithmetic on the vector pipe, and in the
-// next phase they swap.  The two waves that share a SIMD so never want the same pipe at the
-// same time, and only four waves read operands from LDS at any moment.
-//
-//   phase 2t    A: PV(t-1), S(t)       B: softmax(t-1)
-//   phase 2t+1  A: softmax(t)          B: PV(t-1), S(t)
-//
-// Tiles reach LDS without passing through registers (global_load_lds, 16 bytes per lane, a
-// wave's 64 lanes filling 1 KiB of consecutive LDS bytes = 4 token rows), three buffers for the
-// keys and three for the values: K_t sits in key buffer t % 3, V_t in value buffer t % 3.  At
-// During tile step t (behind its softmax arithmetic) every wave asks for its share of
-// (K_{t+2}, V_{t+1}); the buffers they go to held K_{t-1} and V_{t-2}, whose last reader was
-// group B in phase 2t-1, and what is read in phases 2t and 2t+1 (K_t, V_{t-1}) was asked for
-// two tile steps earlier.  Rows are
-// not padded (a load fills consecutive bytes); instead the 16-byte chunks of a row are
-// permuted, which the loading lane does by picking its global address: chunk c of key row r
-// lies at chunk c ^ (r % 16), chunk c of value row r at c ^ 2 (r % 8) -- the same bank spread
-// as the padded rows of the kernel above (16 key rows / 8 value rows hit different banks).
-// ------------------------------------------------------------------------------------------
-constexpr int kPpThreads = 512;
-constexpr int kPpQTile = 2 * kPfQTile;
-
-// s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and
-// 15:14, the other counters left at their maxima)
-template <int N>
-__device__ __forceinline__ void pf_wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-template <typename E, bool kWrite>
-__global__ __launch_bounds__(kPpThreads, 1) __attribute__((amdgpu_waves_per_eu(2, 2))) void fs_prefill_attn_pp_kernel(
-    const char *__restrict__ q, const char *__restrict__ k, const char *__restrict__ v,
-    const PfItem *__restrict__ items, float *__restrict__ out, int32_t H, float scale_log2e,
-    char *__restrict__ pool, const int32_t *__restrict__ table, int32_t table_stride, int32_t num_blocks,
-    int32_t *__restrict__ err)
-{
-    constexpr int D = 128;
-    constexpr int kRow = D * 2;      // bytes per staged row
-    constexpr int NC = D / 16;
-    constexpr int ND = D / 32;
-    constexpr int kChunks = D / 8;   // 16-byte chunks per row
-    constexpr int kTileBytes = kPfKTile * kRow;
-    constexpr int kWaves = kPpThreads / 64;
-    constexpr int kLoadsPerWave = kTileBytes / 1024 / kWaves;  // global_load_lds instructions per wave and tile
-    constexpr int kOutCols = D / 2;
-    constexpr int kOutStride = kOutCols * 4 + 16;
-    static_assert(kLoadsPerWave * kWaves * 1024 == kTileBytes && kChunks == 16, "staging shape");
-    static_assert(kWaves * 32 * kOutStride <= 6 * kTileBytes, "output staging must fit the tile buffers");
-    __shared__ __attribute__((aligned(1024))) char lds[6 * kTileBytes];
-    char *const kbuf = lds;                   // key buffer b at kbuf + b * kTileBytes
-    char *const vbuf = lds + 3 * kTileBytes;  // value buffer b at vbuf + b * kTileBytes
-
-    const int seq = blockIdx.x / kXcds;
-    if (seq >= items[0].t0) return;
-    const PfItem item = items[1 + seq];
-    const int h = (item.qt_group >> 16) * kXcds + blockIdx.x % kXcds;
-    if (h >= H) return;
-    const long long t0 = item.t0;
-    const int s = item.s, qt = item.qt_group & 0xffff;
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int grp = wave >> 2, wq = wave & 3;
-    const int r = lane & 31, hh = lane >> 5;
-    const int row0 = qt * kPpQTile + grp * kPfQTile + wq * 32;
-    const int qrow = row0 + r;
-    const size_t tok_bytes = (size_t)H * D * 2;
-    const size_t head_off = (size_t)h * D * 2;
-    const char *kb = k + (size_t)t0 * tok_bytes + head_off;
-    const char *vb = v + (size_t)t0 * tok_bytes + head_off;
-
-    u32x4 qf[NC];
-    {
-        const char *qb = q + ((size_t)t0 + (size_t)(qrow < s ? qrow : s - 1)) * tok_bytes + head_off;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) qf[c] = *(const u32x4 *)(qb + c * 32 + hh * 16);
-    }
-
-    const int last_row = (qt * kPpQTile + kPpQTile < s ? qt * kPpQTile + kPpQTile : s) - 1;
-    const int nkt = last_row / kPfKTile + 1;  // key tiles the workgroup walks
-    // key tiles this wave takes part in: those that hold a key one of its rows may see
-    int nkt_w = 0;
-    if (row0 < s) {
-        nkt_w = (row0 + 31) / kPfKTile + 1;
-        nkt_w = nkt_w < nkt ? nkt_w : nkt;
-    }
-
-    // Staging: load number i of this wave covers the LDS bytes [(wave * kLoadsPerWave + i) * 1024, + 1024)
-    // of a tile buffer, i.e. rows 4n .. 4n+3 (n = wave * kLoadsPerWave + i); this lane fills
-    // chunk lane % 16 of row 4n + lane / 16 and fetches the chunk the permutation puts there.  Which
-    // chunk that is does not depend on the tile, so the lane's byte offset from the tile's first
-    // row is computed once; only a tile that reaches past the prompt's end (its last one, if any)
-    // has its rows clamped lane by lane.
-    typedef __attribute__((address_space(3))) void *lds_void_ptr;
-    uint32_t st_off[2][kLoadsPerWave];  // [keys, values][load]: row * tok_bytes + chunk * 16
-    int st_rowc[2][kLoadsPerWave];      // row | chunk << 8, for the clamped path
-#pragma unroll
-    for (int i = 0; i < kLoadsPerWave; ++i) {
-        const int n = wave * kLoadsPerWave + i;
-        const int row = 4 * n + (lane >> 4);
-        const int cp = lane & 15;
-        const int ck = cp ^ (row & 15), cv = cp ^ (2 * (row & 7));
-        st_off[0][i] = (uint32_t)((size_t)row * tok_bytes) + ck * 16;
-        st_off[1][i] = (uint32_t)((size_t)row * tok_bytes) + cv * 16;
-        st_rowc[0][i] = row | (ck << 8);
-        st_rowc[1][i] = row | (cv << 8);
-    }
-    // (the loads are written as assembly so that the compiler does not tie the LDS reads of the
-    // running step to them: the waits for them are placed by hand, see begin_step)
-    auto stage_tile = [&](const char *base, int kt, char *buf, int which) __attribute__((always_inline)) {
-        const char *tile = base + (size_t)kt * kPfKTile * tok_bytes;  // wave-uniform
-        const bool whole = kt * kPfKTile + kPfKTile <= s;
-#pragma unroll
-        for (int i = 0; i < kLoadsPerWave; ++i) {
-            const int n = wave * kLoadsPerWave + i;
-            const uint32_t dst = (uint32_t)(size_t)(lds_void_ptr)(buf + n * 1024);
-            uint32_t off = st_off[which][i];
-            if (!whole) {
-                int grow = kt * kPfKTile + (st_rowc[which][i] & 255);
-                grow = (grow < s ? grow : s - 1) - kt * kPfKTile;  // >= 0: a staged tile starts inside the prompt
-                off = (uint32_t)((size_t)grow * tok_bytes) + (st_rowc[which][i] >> 8) * 16;
-            }
-            uint32_t m0_saved;
-            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-                         : "=&s"(m0_saved)
-                         : "s"(dst), "v"(off), "s"(tile)
-                         : "memory");
-        }
-    };
-
-    pf_f32x16 o[ND];
-#pragma unroll
-    for (int t = 0; t < ND; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
-    float m = -INFINITY, l = 0.f;
-    pf_f32x16 sc[2];
-    uint32_t pb[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pb[i][e] = 0u;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) sc[0][e] = 0.f, sc[1][e] = 0.f;
-
-    // operand addresses inside a tile buffer (see the permutation above)
-    int k_off[NC];  // key row r (and 32 + r), chunk 2c + hh
-    {
-        const int k_xor = (hh * 16) ^ ((r & 15) * 16);
-#pragma unroll
-        for (int c = 0; c < NC; ++c) k_off[c] = r * kRow + (k_xor ^ (c * 32));
-    }
-    int v_off[ND];  // value row of this lane in a group of 16 rows, 32-byte granule of output tile j
-    {
-        const int v_row = 4 * hh + ((lane & 15) >> 2);
-        const int v_xor = ((((lane >> 4) & 1) ^ (v_row & 7)) * 32);
-#pragma unroll
-        for (int j = 0; j < ND; ++j) v_off[j] = v_row * kRow + 8 * (lane & 3) + (v_xor ^ (j * 64));
-    }
-
-    // matrix work of tile step t: PV(t-1) from value buffer vs, then S(t) from key buffer ks.  The
-    // LDS reads run ahead of the matrix instructions that use them, across the two parts: the
-    // first key operands are asked for while the last value operands multiply.
-    auto mwork = [&](int t, const char *ks, const char *vs) __attribute__((always_inline)) {
-        const bool has_pv = t >= 1 && t - 1 < nkt_w;
-        const bool has_s = t < nkt_w;
-        u32x4 a[NC];
-        if (has_pv) {
-            typedef pf_i16x4 __attribute__((address_space(3))) * lds_i16x4_ptr;
-            auto v_operand = [&](int i) __attribute__((always_inline)) {
-                const char *p0 = vs + v_off[i % ND] + (16 * (i / ND)) * kRow;
-                const pf_i16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)p0);
-                const pf_i16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(p0 + 8 * kRow));
-                const pf_u32x2 w0 = __builtin_bit_cast(pf_u32x2, a0), w1 = __builtin_bit_cast(pf_u32x2, a1);
-                return u32x4{w0.x, w0.y, w1.x, w1.y};
-            };
-#pragma unroll
-            for (int c = 0; c < NC; ++c) a[c] = v_operand(c);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 4 * ND; ++i) {
-                const int kc = i / ND;
-                const u32x4 pv = u32x4{pb[kc][0], pb[kc][1], pb[kc][2], pb[kc][3]};
-                o[i % ND] = PfMath<E>::mfma(a[i % NC], pv, o[i % ND]);
-                if (i + NC < 4 * ND) a[i % NC] = v_operand(i + NC);
-                else if (has_s) a[i % NC] = *(const u32x4 *)(ks + k_off[i % NC]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (has_s) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sc[0][e] = 0.f, sc[1][e] = 0.f;
-            if (!has_pv) {
-#pragma unroll
-                for (int c = 0; c < NC; ++c) a[c] = *(const u32x4 *)(ks + k_off[c]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                sc[0] = PfMath<E>::mfma(a[c], qf[c], sc[0]);
-                a[c] = *(const u32x4 *)(ks + 32 * kRow + k_off[c]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int c = 0; c < NC; ++c) sc[1] = PfMath<E>::mfma(a[c], qf[c], sc[1]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    // softmax arithmetic of tile step t: scores -> probabilities (rounded), running maximum and sum
-    auto softmax = [&](int t) __attribute__((always_inline)) {
-        if (t < 0 || t >= nkt_w) return;
-        const int key0 = t * kPfKTile;
-        if (key0 + kPfKTile - 1 > row0) {  // wave-uniform: the tile crosses the diagonal
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = key0 + kh * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    if (key > qrow) sc[kh][e] = -INFINITY;
-                }
-        }
-        float mx = sc[0][0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sc[0][e]);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[1][e]);
-        mx = fmaxf(mx, pf_other_half(mx));
-        const float m_new = fmaxf(m, mx * scale_log2e);  // finite: key 0 is visible to every row
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
-        l *= alpha;
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[kh][e], scale_log2e, -m_new));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[kh][e + 1], scale_log2e, -m_new));
-                const uint32_t pk = PfMath<E>::pack2(p0, p1);
-                l = PfMath<E>::add_pair(pk, l);  // the denominator sums what the matrix cores will multiply
-                pb[kh * 2 + (e >> 3)][(e & 7) >> 1] = pk;
-            }
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {  // wave-uniform
-#pragma unroll
-            for (int t2 = 0; t2 < ND; ++t2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[t2][e] *= alpha;
-        }
-    };
-    // kWrite: the rows of key or value tile kt, staged in `buf`, go to the pool (the tile's tokens
-    // are this workgroup's rows).  Keys: lane -> slot, so that 16 lanes fill the 256 contiguous
-    // bytes of one d/8 chunk of a block; values: 16 lanes copy one row.
-    auto write_tile = [&](int kt, const char *buf, bool values) __attribute__((always_inline)) {
-        const size_t chunk = (size_t)kBlockTokens * D * 2;
-        const int32_t *trow = table + (size_t)item.job * table_stride;
-        const int lo = threadIdx.x % kBlockTokens, rest = threadIdx.x / kBlockTokens;
-        constexpr int kPieces = kPfKTile * kChunks / kPpThreads;
-#pragma unroll
-        for (int p = 0; p < kPieces; ++p) {
-            const int piece = rest + p * (kPpThreads / kBlockTokens);
-            // keys: piece = (block in tile, chunk), lo = slot; values: piece = row in tile, lo = chunk
-            const int row = values ? piece : (piece / kChunks) * kBlockTokens + lo;
-            const int ch = values ? lo : piece % kChunks;
-            const int pos = kt * kPfKTile + row;
-            if (pos < s) {
-                const int bid = pos / kBlockTokens < table_stride ? trow[pos / kBlockTokens] : -1;
-                if ((uint32_t)bid < (uint32_t)num_blocks) {
-                    char *blk = pool + (size_t)bid * (2 * (size_t)H * chunk);
-                    if (values)
-                        *(u32x4 *)(blk + ((size_t)H + h) * chunk + (size_t)(pos % kBlockTokens) * kRow + ch * 16) =
-                            *(const u32x4 *)(buf + row * kRow + (ch ^ (2 * (row & 7))) * 16);
-                    else
-                        *(u32x4 *)(blk + (size_t)h * chunk + ((size_t)ch * kBlockTokens + (pos % kBlockTokens)) * 16) =
-                            *(const u32x4 *)(buf + row * kRow + (ch ^ (row & 15)) * 16);
-                } else if (values && ch == 0 && h == 0) {
-                    atomicOr(err, kErrBadBlock);
-                }
-            }
-        }
-    };
-
-    // prologue: what phases -4 and -2 would have asked for
-    stage_tile(kb, 0, kbuf, 0);
-    if (1 < nkt) stage_tile(kb, 1, kbuf + kTileBytes, 0);
-    stage_tile(vb, 0, vbuf, 1);
-    int b_cur = 0, b_nxt = 1, b_prv = 2;  // t % 3, (t + 1) % 3, (t + 2) % 3 == (t - 1) % 3
-    // start of phase 2t, the same for both groups
-    auto begin_step = [&](int t) __attribute__((always_inline)) {
-        // what this wave asked for in the previous step (K_{t+1}, V_t) may stay in flight; everything
-        // older -- K_t and V_{t-1} among it -- has to be in LDS before the barrier lets anyone read it
-        if (!kWrite && t + 1 < nkt) pf_wait_vmcnt<2 * kLoadsPerWave>();
-        else pf_wait_vmcnt<0>();
-        __syncthreads();  // the readers of K_{t-1} and V_{t-2} are done, K_t and V_{t-1} are visible
-        if (kWrite) {
-            if (t < nkt && (t >> 2) == qt) write_tile(t, kbuf + b_cur * kTileBytes, false);
-            if (t >= 1 && ((t - 1) >> 2) == qt) write_tile(t - 1, vbuf + b_prv * kTileBytes, true);
-        }
-    };
-    // This wave's share of (K_{t+2}, V_{t+1}) is asked for at some point of tile step t, after the
-    // step's first barrier: each group does it behind its softmax arithmetic, where it has time.
-    auto stage_step = [&](int t) __attribute__((always_inline)) {
-        if (t + 2 < nkt) stage_tile(kb, t + 2, kbuf + b_prv * kTileBytes, 0);
-        if (t + 1 < nkt) stage_tile(vb, t + 1, vbuf + b_nxt * kTileBytes, 1);
-    };
-    auto rotate = [&]() __attribute__((always_inline)) {
-        const int b = b_prv;
-        b_prv = b_cur;
-        b_cur = b_nxt;
-        b_nxt = b;
-    };
-    // (the two groups run the same number of barriers; each has its own loop so that the
-    // accumulators are updated along one straight path)
-    if (grp == 0) {
-        for (int t = 0; t <= nkt; ++t) {
-            begin_step(t);
-            mwork(t, kbuf + b_cur * kTileBytes, vbuf + b_prv * kTileBytes);
-            __syncthreads();  // phase 2t+1
-            softmax(t);
-            stage_step(t);
-            rotate();
-        }
-    } else {
-        for (int t = 0; t <= nkt; ++t) {
-            begin_step(t);
-            softmax(t - 1);
-            stage_step(t);
-            __syncthreads();  // phase 2t+1
-            mwork(t, kbuf + b_cur * kTileBytes, vbuf + b_prv * kTileBytes);
-            rotate();
-        }
-    }
-
-    l += pf_other_half(l);
-    const float inv = 1.f / l;
-    __syncthreads();  // the tile buffers are free
-    char *const stage = lds + wave * (32 * kOutStride);
-    constexpr int kLanesPerRow = kOutCols / 4;
-    constexpr int kRowsPerStore = 64 / kLanesPerRow;
     const int out_row = lane / kLanesPerRow, out_col = (lane % kLanesPerRow) * 4;
     float *const ob = out + ((size_t)t0 + row0) * ((size_t)H * D) + (size_t)h * D;
 #pragma unroll
