@@ -568,7 +568,7 @@ def main():
     ap.add_argument("--footprint-gb", type=float, default=2.0, help="bytes touched between reuses of a replica")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
-                    help="pool knob for every pool of the run (fs_pool_set_param), e.g. split_unit_cost=4")
+                    help="pool knob for every pool of the run (fs_pool_set_param), e.g. merge_in_kernel=1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-swap-overlap", action="store_true", help="skip the steps timed beside block swaps")
