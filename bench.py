@@ -274,6 +274,34 @@ def read_ceiling(fs, torch, nbytes=4 << 30, reps=5):
     return best
 
 
+def same_bytes_read(fs, torch, sizes, reps=40):
+    """What a kernel that does nothing but read costs at the presets' own sizes: for every byte
+    count in `sizes`, the median duration of fs_stream_read's kernel over that many bytes, on the
+    attention kernel's grid (one 256-thread workgroup per compute unit), every launch on the
+    next region of a buffer of 4 GiB or more (a size far beyond the caches is simply read
+    again).  The duration comes from events attached to the launch, as the attention kernel's."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    big = torch.empty(max(4 << 30, max(int(n) for n in sizes) + 4096), dtype=torch.uint8, device="cuda")
+    big.zero_()
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    out = []
+    for n in sizes:
+        nbytes = max(4096, int(n) // 4096 * 4096)
+        step = (nbytes + (64 << 20)) // 4096 * 4096
+        off, ts = 0, []
+        for _ in range(reps + 5):
+            if off + nbytes > big.numel():
+                off = 0
+            ts.append(fs.fs_stream_read_timed(big[off:off + nbytes], sink, cus))
+            off += step
+        ts = sorted(ts[5:])
+        us = ts[len(ts) // 2]
+        out.append({"bytes": nbytes, "kernel_us": us, "kernel_us_min": ts[0], "gbps": nbytes / us / 1e3})
+    del big
+    torch.cuda.empty_cache()
+    return out
+
+
 def time_steps_warm(torch, reps, steps, warmup):
     """The same step on ONE pool every time: its blocks stay in the 256 MB last-level cache
     between steps.  Reported beside the headline and labelled as such, never as the headline."""
@@ -746,6 +774,11 @@ def main():
         for r in [line] + others:
             r["roofline"]["practical_read_ceiling_gbps"] = ceil
             r["roofline"]["frac_of_practical_ceiling"] = r["roofline"]["achieved"] / ceil
+        # the same bytes read by a kernel that does nothing else: what the size itself allows
+        rows = [line] + others
+        for r, sr in zip(rows, same_bytes_read(fs, torch, [r["roofline"]["alg_bytes_per_launch"] for r in rows])):
+            sr["attention_kernel_over_plain_read"] = r["roofline"]["kernel_ms"] * 1e3 / sr["kernel_us"]
+            r["roofline"]["plain_read_of_same_bytes"] = sr
     if not args.no_swap_overlap:
         line["swap_overlap"] = [swap_overlap(fs, torch, wl, config_of(i), log) for i in (1, 3)
                                 if config_of(i).dtype != "f32"]

@@ -298,6 +298,12 @@ int fs_pool_last_plan(fs_pool *pool, int32_t num_jobs, int32_t *step_base, void 
  * byte counters.  sink: 16 writable device bytes. */
 int fs_stream_read(const void *src, size_t bytes, void *sink, int32_t workgroups, void *stream);
 int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups, void *stream);
+/* fs_stream_read that waits for its kernel and reports the kernel's own duration in
+ * microseconds in *kernel_us (host pointer), taken from events attached to the launch: the
+ * span a profiler reports for the dispatch, and the way the duration of a profiled pool's
+ * kernels is taken, so that the two compare like for like. */
+int fs_stream_read_timed(const void *src, size_t bytes, void *sink, int32_t workgroups, void *stream,
+                         float *kernel_us);
 
 const char *fs_strerror(int status);
 const char *fs_version(void);

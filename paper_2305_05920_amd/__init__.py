@@ -28,7 +28,7 @@ EXPORTS = (
     "fs_prefill_attention", "fs_prefill_step",
     "fs_decode_attention", "fs_decode_attention_static", "fs_decode_step", "fs_pool_offload", "fs_pool_upload", "fs_profile_enable",
     "fs_profile_collect", "fs_pool_set_param", "fs_pool_get_param", "fs_pool_last_plan",
-    "fs_stream_read", "fs_stream_copy", "fs_strerror", "fs_version",
+    "fs_stream_read", "fs_stream_read_timed", "fs_stream_copy", "fs_strerror", "fs_version",
 )
 
 
@@ -87,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.fs_pool_get_param.argtypes = [vp, ctypes.c_char_p, P(i32)]
     lib.fs_pool_last_plan.argtypes = [vp, i32, vp, vp]
     lib.fs_stream_read.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
+    lib.fs_stream_read_timed.argtypes = [vp, ctypes.c_size_t, vp, i32, vp, ctypes.POINTER(ctypes.c_float)]
     lib.fs_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, i32, vp]
     lib.fs_strerror.argtypes = [ctypes.c_int]
     lib.fs_strerror.restype = ctypes.c_char_p
@@ -378,6 +379,15 @@ def fs_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int, strea
     """Reads every byte of `src` once (measurement helper)."""
     _ok(load_library().fs_stream_read(_dev(src, "src"), src.numel() * src.element_size(), _dev(sink, "sink"),
                                       int(workgroups), _stream_ptr(stream)), "fs_stream_read")
+
+
+def fs_stream_read_timed(src: torch.Tensor, sink: torch.Tensor, workgroups: int, stream=None) -> float:
+    """fs_stream_read, waited for; returns the kernel's own duration in microseconds."""
+    us = ctypes.c_float(0.0)
+    _ok(load_library().fs_stream_read_timed(_dev(src, "src"), src.numel() * src.element_size(), _dev(sink, "sink"),
+                                            int(workgroups), _stream_ptr(stream), ctypes.byref(us)),
+        "fs_stream_read_timed")
+    return float(us.value)
 
 
 def fs_stream_copy(dst: torch.Tensor, src: torch.Tensor, workgroups: int, stream=None) -> None:

@@ -1699,6 +1699,32 @@ int fs_stream_read(const void *src, size_t bytes, void *sink, int32_t workgroups
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
+int fs_stream_read_timed(const void *src, size_t bytes, void *sink, int32_t workgroups, void *stream,
+                         float *kernel_us)
+{
+    if (!src || !sink || !kernel_us || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) ||
+        ((uintptr_t)sink & 15) || workgroups < 1 || workgroups > (1 << 20))
+        return FS_ERR_INVALID_ARG;
+    hipEvent_t start = nullptr, stop = nullptr;
+    if (hipEventCreate(&start) != hipSuccess) return FS_ERR_HIP;
+    if (hipEventCreate(&stop) != hipSuccess) {
+        (void)hipEventDestroy(start);
+        return FS_ERR_HIP;
+    }
+    // the events ride on the launch itself, as those of a profiled pool's kernels do: the
+    // runtime stamps them with the dispatch's own start and end
+    hipExtLaunchKernelGGL(fs_stream_read_kernel, dim3((unsigned)workgroups), dim3(kThreads), 0, (hipStream_t)stream,
+                          start, stop, 0, (const u32x4 *)src, bytes / 16, (u32x4 *)sink);
+    int rc = hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+    float ms = 0.f;
+    if (rc == FS_OK && (hipEventSynchronize(stop) != hipSuccess || hipEventElapsedTime(&ms, start, stop) != hipSuccess))
+        rc = FS_ERR_HIP;
+    (void)hipEventDestroy(start);
+    (void)hipEventDestroy(stop);
+    if (rc == FS_OK) *kernel_us = ms * 1e3f;
+    return rc;
+}
+
 int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups, void *stream)
 {
     if (!src || !dst || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||

@@ -538,6 +538,23 @@ def test_kernel_timing_records():
         run.close()
 
 
+def test_plain_read_kernel_reports_its_own_duration():
+    # the measurement helper: a read of 256 MiB takes a time that a GPU's memory can deliver
+    # (between 2 and 16 TB/s on any HBM part), a bad argument is refused before any launch
+    import paper_2305_05920_amd as fs
+    src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    fs.fs_stream_read(src, sink, 256)
+    torch.cuda.synchronize()
+    us = [fs.fs_stream_read_timed(src, sink, 256) for _ in range(3)]
+    assert all(16.0 < t < 130.0 for t in us), us
+    assert not sink.cpu().numpy().any()
+    with pytest.raises(fs.FsError):
+        fs.fs_stream_read_timed(src[:24], sink, 256)   # not a multiple of 16 bytes
+    with pytest.raises(fs.FsError):
+        fs.fs_stream_read_timed(src, sink, 0)
+
+
 def test_two_pools_on_two_streams_at_once_match_their_serial_results():
     # a pool is not thread-safe, but different pools may run at the same time: the decode step of
     # two batches on two streams, launched back to back without a wait in between, ten times
