@@ -170,7 +170,7 @@ struct AttnShape {
     int32_t num_blocks;
     float scale_log2e;
     int32_t merge;  // 1: the partition pass merges cut pairs itself (no combine launch follows)
-    int32_t trim;   // 1: long batches use 7 of every 8 workgroups (see active_workgroups)
+    int32_t trim;   // 1, 2: long batches use fewer workgroups than were launched (see active_workgroups)
 };
 
 enum : int32_t { kErrBadBlock = 1, kErrBadLen = 2 };
@@ -191,8 +191,18 @@ __device__ __forceinline__ long long wave_of_unit(long long u, long long S, long
 // 1.5-2 % faster that way (the memory system is slightly oversubscribed by a workgroup on
 // every compute unit); short ones need every wave, because a wave's share is a few whole
 // units and one unit more or less is a large step.
+// trim == 2: the grid was launched at two workgroups per compute unit (the fused kernel's
+// default, which short and middling batches want); a batch of at least 32 units per wave of
+// half that grid is handed to the first 7/16 of it, the workgroups that were dispatched first,
+// one to a compute unit (long_context preset: step 902 against 919 us; at 12 units per wave
+// the two-per-unit grid is still the faster one).
 __device__ __forceinline__ int active_workgroups(long long S, int G, int trim)
 {
+    if (trim == 2) {
+        const int half = G / 2;
+        if (half < 8 * kXcds || S < 32LL * half * kWavesPerWg) return G;
+        return half * 7 / 8 / kXcds * kXcds;
+    }
     if (!trim || G < 8 * kXcds || S < 8LL * G * kWavesPerWg) return G;
     return G * 7 / 8 / kXcds * kXcds;
 }
@@ -1206,12 +1216,14 @@ int launch_attention(fs_pool *p, const AttnScratch &sc, const void *q, const voi
     // device, where the lengths are known); two per compute unit for the fused kernel.
     const long long persistent =
         (long long)p->num_cus * (p->wgs_per_cu > 0 ? p->wgs_per_cu : (kFused ? 2 : 1));
-    sh.trim = (p->wgs_per_cu == 0 && !kFused) ? 1 : 0;
     if (wgs > persistent) wgs = persistent;
     if (p->max_workgroups > 0 && wgs > p->max_workgroups) wgs = p->max_workgroups;
     if (sc.is_static && wgs > kStaticWorkgroups) wgs = kStaticWorkgroups;
     if (wgs < 1) wgs = 1;
     if (wgs * kWavesPerWg > sc.waves_cap) return FS_ERR_INVALID_ARG;
+    // default grids hand long batches to fewer workgroups (decided on the device, where the
+    // lengths are known); the fused kernel's rule assumes the full two-per-unit grid
+    sh.trim = p->wgs_per_cu != 0 ? 0 : !kFused ? 1 : (wgs == 2LL * p->num_cus ? 2 : 0);
     // fs_decode_step: the new tokens' rows are written by the attention kernel itself only
     // where no second launch follows (merge mode) or on request; otherwise by that launch
     const bool write_in_kernel = kFused && (sh.merge || p->append_in_attention);
