@@ -291,11 +291,12 @@ int fs_pool_get_param(const fs_pool *pool, const char *name, int32_t *value);
  * helper; num_jobs at most 1024 (the last launch slice of a larger batch). */
 int fs_pool_last_plan(fs_pool *pool, int32_t num_jobs, int32_t *step_base, void *stream);
 
-/* Plain streaming kernels of known size (not part of the decode path): a read of
- * `bytes` from src and a copy of `bytes` from src to dst, device pointers, 16-byte
+/* Plain streaming kernels of known size: a read of `bytes` from src and a copy of `bytes`
+ * from src to dst, pointers the GPU can reach (device memory, or pinned host memory), 16-byte
  * aligned, bytes a multiple of 16, on `workgroups` workgroups of 256 threads.  They
  * give the practical HBM ceiling of the GPU at hand and the scale of the hardware
- * byte counters.  sink: 16 writable device bytes. */
+ * byte counters; the cache manager brings a batch's tables from pinned memory to the GPU
+ * with the copy (fs_kvm_stage_batch).  sink: 16 writable device bytes. */
 int fs_stream_read(const void *src, size_t bytes, void *sink, int32_t workgroups, void *stream);
 int fs_stream_copy(void *dst, const void *src, size_t bytes, int32_t workgroups, void *stream);
 /* fs_stream_read that waits for its kernel and reports the kernel's own duration in

@@ -127,8 +127,9 @@ int fs_kvm_table_rows(const fs_kvm *kvm, const int64_t *job_ids, int32_t n, int3
 
 /* The device-side inputs of one batch: table rows, lengths (tokens cached) and n_extra
  * caller words (e.g. prompt token offsets) of the n jobs are written into a pinned staging
- * slot and copied to the GPU with one asynchronous copy on the manager's staging stream;
- * `stream` (the stream the kernels will run on) is made to wait for that copy on the GPU.
+ * slot and brought to the GPU by a small copy kernel launched on `stream`, the stream the
+ * kernels will run on (every call on one manager names the same stream): the words are in
+ * place, in stream order, before anything launched on it afterwards.
  * *d_table, *d_lens, *d_extra receive device pointers that stay valid until 47 later
  * batches have been staged.  Needs layers; n <= max_batch, n_extra <= max_staged_extra. */
 int fs_kvm_stage_batch(fs_kvm *kvm, const int64_t *job_ids, int32_t n, const int32_t *extra, int32_t n_extra,

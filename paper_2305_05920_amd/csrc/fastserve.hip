@@ -975,8 +975,9 @@ __global__ __launch_bounds__(kThreads) void fs_kv_prefill_kernel(
 
 // ------------------------------------------------------------------------------------
 // Plain streaming kernels of known size: the practical HBM ceiling on this GPU and the
-// scale factor of the hardware byte counters.  Not part of the decode path.  Loads and
-// stores carry the non-temporal hint, as the decode kernel's cache reads do.
+// scale factor of the hardware byte counters; the copy also carries a batch's tables from
+// pinned host memory to the GPU for the cache manager.  Loads and stores carry the
+// non-temporal hint, as the decode kernel's cache reads do.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void fs_stream_read_kernel(const u32x4 *__restrict__ src, size_t nvec,
                                                                   u32x4 *__restrict__ sink)
@@ -1590,14 +1591,23 @@ static int copy_blocks(fs_pool *p, const int32_t *block_ids, const int32_t *host
         }
         return FS_OK;
     }
-    // runs of consecutive (block id, host slot) pairs travel as one copy
+    // Runs of (block id, host slot) pairs that step together, both up by one or both down by one,
+    // are one stretch of memory on either side and travel as one copy.  (A manager that takes
+    // ids from the top of a free stack hands out descending runs.)
     int i = 0;
     while (i < n) {
-        int run = 1;
-        while (i + run < n && block_ids[i + run] == block_ids[i] + run && host_slots[i + run] == host_slots[i] + run)
-            ++run;
-        char *dev = p->mem + (size_t)block_ids[i] * p->block_bytes;
-        char *host = p->host_mem + (size_t)host_slots[i] * p->block_bytes;
+        int run = 1, d = 0;
+        if (i + 1 < n) {
+            const int db = block_ids[i + 1] - block_ids[i], ds = host_slots[i + 1] - host_slots[i];
+            if (db == ds && (db == 1 || db == -1)) d = db;
+        }
+        if (d)
+            while (i + run < n && block_ids[i + run] == block_ids[i] + d * run &&
+                   host_slots[i + run] == host_slots[i] + d * run)
+                ++run;
+        const int first = d < 0 ? i + run - 1 : i;  // the pair at the run's lowest addresses
+        char *dev = p->mem + (size_t)block_ids[first] * p->block_bytes;
+        char *host = p->host_mem + (size_t)host_slots[first] * p->block_bytes;
         hipError_t e = to_host ? hipMemcpyAsync(host, dev, p->block_bytes * run, hipMemcpyDeviceToHost, s)
                                : hipMemcpyAsync(dev, host, p->block_bytes * run, hipMemcpyHostToDevice, s);
         if (e != hipSuccess) return FS_ERR_HIP;

@@ -1,8 +1,8 @@
 // Proactive key-value cache manager of FastServe (arXiv 2305.05920, Section 4.2) and the
 // iteration loop that drives scheduler, manager and attention kernels (Section 3.2,
 // Algorithm 1).  C ABI in include/fastserve_kvm.h.  Host code: the only GPU work issued
-// here is block copies (through fs_pool_offload / fs_pool_upload), small staging copies,
-// events and stream waits.
+// here is block copies (through fs_pool_offload / fs_pool_upload), the small copy kernel that
+// brings a batch's tables over (fs_stream_copy), events and stream waits.
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
@@ -37,9 +37,11 @@ struct Swap {
     hipEvent_t done = nullptr;      // recorded on the side stream after the copies (null without layers)
 };
 
-// Staging ring: kStageSlots slots in groups of kStageGroup.  A slot's pinned words and device
-// words are rewritten one whole turn of the ring later; what guards that is kept per group, not
-// per slot, so that staging one batch costs three runtime calls.
+// Staging ring: kStageSlots slots in groups of kStageGroup.  A batch's words are written into a
+// slot's pinned memory and brought to its device memory by a copy kernel on the kernels' own
+// stream (one launch; an asynchronous copy of a few KiB costs the host several times that), so the
+// device words are in order with their readers by themselves.  The pinned words are rewritten
+// one whole turn of the ring later; what guards that is one event per group, not per slot.
 constexpr int kStageSlots = 64;
 constexpr int kStageGroup = 16;
 constexpr int kStageGroups = kStageSlots / kStageGroup;
@@ -47,7 +49,6 @@ constexpr int kStageGroups = kStageSlots / kStageGroup;
 struct StageSlot {
     int32_t *host = nullptr;        // pinned
     int32_t *dev = nullptr;
-    hipEvent_t copied = nullptr;    // the staging copy out of `host` has run
 };
 
 }  // namespace
@@ -62,7 +63,7 @@ struct fs_kvm {
     std::unordered_map<int64_t, JobBlocks> jobs;
     std::deque<Swap> in_flight;                   // issue order
     std::vector<hipEvent_t> spare_events;
-    hipStream_t side = nullptr, staging = nullptr;
+    hipStream_t side = nullptr;
     hipEvent_t fence = nullptr;                   // compute stream -> side stream
     StageSlot ring[kStageSlots];
     hipEvent_t group_used[kStageGroups] = {};     // the kernels' stream has passed every batch of the group
@@ -170,15 +171,13 @@ int fs_kvm_create(const fs_kvm_config *cfg, fs_pool *const *layers, int32_t num_
     for (int s = cfg->num_host_blocks - 1; s >= 0; --s) k->free_slots.push_back(s);
     if (num_layers) {
         bool ok = hipStreamCreateWithFlags(&k->side, hipStreamNonBlocking) == hipSuccess &&
-                  hipStreamCreateWithFlags(&k->staging, hipStreamNonBlocking) == hipSuccess &&
                   hipEventCreateWithFlags(&k->fence, hipEventDisableTiming) == hipSuccess;
         k->stage_words = (size_t)cfg->max_batch * cfg->table_width + cfg->max_batch + cfg->max_staged_extra;
-        const size_t bytes = std::max<size_t>(k->stage_words, 1) * sizeof(int32_t);
+        const size_t bytes = (std::max<size_t>(k->stage_words, 1) * sizeof(int32_t) + 15) / 16 * 16;
         for (int i = 0; ok && i < kStageSlots; ++i) {
             StageSlot &s = k->ring[i];
             ok = hipHostMalloc((void **)&s.host, bytes, hipHostMallocDefault) == hipSuccess &&
-                 hipMalloc((void **)&s.dev, bytes) == hipSuccess &&
-                 hipEventCreateWithFlags(&s.copied, hipEventDisableTiming) == hipSuccess;
+                 hipMalloc((void **)&s.dev, bytes) == hipSuccess;
         }
         for (int g = 0; ok && g < kStageGroups; ++g)
             ok = hipEventCreateWithFlags(&k->group_used[g], hipEventDisableTiming) == hipSuccess;
@@ -196,7 +195,6 @@ int fs_kvm_destroy(fs_kvm *k)
 {
     if (!k) return FS_ERR_INVALID_ARG;
     if (k->side) (void)hipStreamSynchronize(k->side);
-    if (k->staging) (void)hipStreamSynchronize(k->staging);
     for (Swap &s : k->in_flight)
         if (s.done) (void)hipEventDestroy(s.done);
     for (hipEvent_t e : k->spare_events) (void)hipEventDestroy(e);
@@ -204,13 +202,11 @@ int fs_kvm_destroy(fs_kvm *k)
     for (StageSlot &s : k->ring) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.dev) (void)hipFree(s.dev);
-        if (s.copied) (void)hipEventDestroy(s.copied);
     }
     for (hipEvent_t e : k->group_used)
         if (e) (void)hipEventDestroy(e);
     if (k->fence) (void)hipEventDestroy(k->fence);
     if (k->side) (void)hipStreamDestroy(k->side);
-    if (k->staging) (void)hipStreamDestroy(k->staging);
     delete k;
     return FS_OK;
 }
@@ -434,20 +430,15 @@ int fs_kvm_stage_batch(fs_kvm *k, const int64_t *ids, int32_t n, const int32_t *
     const int slot_index = (int)(seq % kStageSlots);
     const int group = slot_index / kStageGroup;
     if (slot_index % kStageGroup == 0) {
-        // Entering a group.  Every kernel that reads the group just left has been given to the
-        // kernels' stream by now: mark that point.
+        // Entering a group.  Everything that reads the group just left -- its copy kernels and the
+        // kernels behind them -- has been given to the kernels' stream by now: mark that point.
         if (seq > 0 && hipEventRecord(k->group_used[(group + kStageGroups - 1) % kStageGroups], s) != hipSuccess)
             return FS_ERR_HIP;
-        if (seq >= kStageSlots) {
-            // This group was used one turn ago.  Its device words may be rewritten once the
-            // kernels' stream has passed the mark set when it was left (the staging stream waits
-            // for that on the GPU); its pinned words once the copies out of them have run (the
-            // host waits: they have, unless the GPU is most of a ring behind -- this bounds the
-            // host's lead over the GPU).
-            if (hipStreamWaitEvent(k->staging, k->group_used[group], 0) != hipSuccess ||
-                hipEventSynchronize(k->ring[slot_index + kStageGroup - 1].copied) != hipSuccess)
-                return FS_ERR_HIP;
-        }
+        // This group was used one turn ago.  Its pinned words may be rewritten once the stream has
+        // passed the mark set when it was left (it has, unless the GPU is most of a ring behind:
+        // this bounds the host's lead over the GPU).  Its device words need no guard: the copy
+        // kernel that rewrites them runs on the same stream, behind their last reader.
+        if (seq >= kStageSlots && hipEventSynchronize(k->group_used[group]) != hipSuccess) return FS_ERR_HIP;
     }
     StageSlot &slot = k->ring[slot_index];
     const int W = k->cfg.table_width;
@@ -456,10 +447,9 @@ int fs_kvm_stage_batch(fs_kvm *k, const int64_t *ids, int32_t n, const int32_t *
     if (rc != FS_OK) return rc;
     for (int r = 0; r < n; ++r) len[r] = (int32_t)k->jobs.at(ids[r]).length;
     if (n_extra) std::memcpy(ext, extra, (size_t)n_extra * sizeof(int32_t));
-    const size_t bytes = ((size_t)k->cfg.max_batch * W + k->cfg.max_batch + n_extra) * sizeof(int32_t);
-    if (hipMemcpyAsync(slot.dev, slot.host, bytes, hipMemcpyHostToDevice, k->staging) != hipSuccess ||
-        hipEventRecord(slot.copied, k->staging) != hipSuccess || hipStreamWaitEvent(s, slot.copied, 0) != hipSuccess)
-        return FS_ERR_HIP;
+    const size_t bytes = (((size_t)k->cfg.max_batch * W + k->cfg.max_batch + n_extra) * sizeof(int32_t) + 15) / 16 * 16;
+    const int wgs = (int)((bytes / 16 + 255) / 256);
+    if (fs_stream_copy(slot.dev, slot.host, bytes, wgs, stream) != FS_OK) return FS_ERR_HIP;
     k->staged += 1;
     *d_table = slot.dev;
     *d_lens = slot.dev + (size_t)k->cfg.max_batch * W;

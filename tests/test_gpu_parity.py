@@ -519,6 +519,33 @@ def test_library_allocated_pool_and_raw_block_copies():
         assert np.array_equal(pool.read_block(5, np.float32), a)
 
 
+@pytest.mark.parametrize("engine", [0, 1])
+def test_block_copies_in_rising_falling_and_broken_runs(engine):
+    # pairs that step together (up or down) travel as one copy each; every block must still land
+    # in the slot it was paired with, and come back into the block it is paired with
+    import paper_2305_05920_amd as fs
+    with fs.Pool("bf16", 3, 64, 24, num_host_blocks=16) as pool:
+        pool.set_param("swap_engine", engine)
+        rng = np.random.default_rng(5)
+        words = pool.block_bytes // 2
+        data = {b: rng.integers(0, 1 << 16, size=words, dtype=np.uint16) for b in range(24)}
+        for b, a in data.items():
+            pool.write_block(b, a)
+        blocks = [7, 6, 5, 4, 10, 11, 12, 20, 2, 1, 15, 17, 16]   # falling, rising, single, falling, broken, falling
+        slots = [9, 8, 7, 6, 0, 1, 2, 15, 4, 3, 10, 12, 11]
+        fs.fs_pool_offload(pool, blocks, slots)
+        torch.cuda.synchronize()
+        for b in blocks:
+            pool.write_block(b, np.zeros(words, dtype=np.uint16))
+        back = [b + 1 if b in (20,) else b for b in blocks][::-1]    # same blocks, pairs listed the other way round
+        fs.fs_pool_upload(pool, slots[::-1], back)
+        torch.cuda.synchronize()
+        for b_src, b_dst in zip(blocks[::-1], back):
+            assert np.array_equal(pool.read_block(b_dst, np.uint16), data[b_src]), (b_src, b_dst)
+        for b in set(range(24)) - set(blocks) - set(back):
+            assert np.array_equal(pool.read_block(b, np.uint16), data[b])
+
+
 def test_kernel_timing_records():
     cfg = wl.CONFIGS[0]
     case = hs.make_case(cfg, 0)
