@@ -428,7 +428,14 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
     };
     int L = __builtin_amdgcn_readfirstlane(s_len[j]);
     int steps = steps_of(L);
-    int NB = (L + kBlockTokens - 1) / kBlockTokens;
+    // Blocks of the job as the loads address them.  Fused, a job with an empty cache still has
+    // its one unit: it counts as one block with one slot for addressing (weight zero: the score
+    // mask goes by the true length), so that no load needs a clamp of its own at zero.
+    auto blocks_of = [](int len) {
+        const int n = (len + kBlockTokens - 1) / kBlockTokens;
+        return (kFused && n == 0) ? 1 : n;
+    };
+    int NB = blocks_of(L);
     int h, k;
     {
         const int local = (int)(lo - (long long)__builtin_amdgcn_readfirstlane(s_base[j]) * H);
@@ -480,8 +487,7 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
     // block 4*kk+r of the job, or the job's last block for rows past it.
     auto row_block = [&](int kk) -> int {
         int bi = kStepBlocks * kk + r;
-        bi = bi < NB ? bi : NB - 1;
-        if (kFused) bi = bi > 0 ? bi : 0;  // a job with an empty cache: entry 0, the block of its new token
+        bi = bi < NB ? bi : NB - 1;  // (fused, empty cache: entry 0, the block of the job's new token)
         int bid = w_tbl[bi - kStepBlocks * kt];
         if ((uint32_t)bid >= (uint32_t)sh.num_blocks) {
             // never dereferenced: block 0 is read instead and the flag raised
@@ -500,8 +506,8 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
             const int bb = __builtin_amdgcn_readlane(bidv, 16 * b);
             int bi = kStepBlocks * kk + b;
             bi = bi < NBB ? bi : NBB - 1;
-            if (kFused) bi = bi > 0 ? bi : 0;
-            int left = LL - bi * kBlockTokens;  // valid slots of that block (>= 1 unless the cache is empty)
+            int left = LL - bi * kBlockTokens;  // valid slots of that block
+            if (kFused) left = left > 0 ? left : 1;  // (wave-uniform; zero only for an empty cache)
             const char *vp = pool + (size_t)bb * block_bytes + (size_t)(H + hh) * kChunkBytes + (size_t)vc * 16;
             // fused, empty cache: nothing of this job is in the pool yet; the loads read the
             // job's own new value row instead (finite data, weight zero), slot 0 below
@@ -510,7 +516,6 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
             for (int i = 0; i < NV; ++i) {
                 int slot = i * TPI + vt;
                 slot = slot < left ? slot : left - 1;
-                if (kFused) slot = slot > 0 ? slot : 0;
                 vr[b][i] = load_stream(vp + (size_t)slot * kRowBytes);
             }
         }
@@ -576,7 +581,7 @@ __global__ __launch_bounds__(kThreads) void fs_attn_partition_kernel(
                     j = nj;
                     L = nL;
                     steps = steps_of(L);
-                    NB = (L + kBlockTokens - 1) / kBlockTokens;
+                    NB = blocks_of(L);
                     trow = table + (size_t)j * sh.table_stride;
                     kt = 0;
                     store_window(ntbl, ntbl_nx);
